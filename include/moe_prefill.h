@@ -1,0 +1,179 @@
+/* moe_prefill.h -- C ABI of the MI355X (gfx950) MoE prefill block.
+ *
+ * The block is the per-layer Mixture-of-Experts computation that one GPU runs
+ * locally when the whole expert set of the current layer is resident on it, as in
+ * the paper's asynchronous expert-parallel backend (Sec. 6.2: every GPU evaluates
+ * the current MoE layer entirely on-device; Sec. 1: dispatch becomes a local
+ * operation).  Sec. 2.3 defines the computation: E experts, each a two-layer MLP;
+ * a router sends each token to its top-k experts and their outputs are summed.
+ * The "auxiliary" token permutation/alignment steps that Sec. 4.3 places on the
+ * critical path of every layer are moe_permute here.
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is DEVICE memory owned by the caller, on the device that
+ *     is current when the call is made.  The library allocates nothing, frees
+ *     nothing and keeps no pointer after the call's kernels have run.  Scratch
+ *     space comes in through (ws, ws_bytes); its minimum size is
+ *     moe_workspace_bytes(cfg, call).  ws must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work: no host synchronisation and no device-to-host copy.
+ *   - Tensors are dense row-major; "[A,B]" lists dimensions slowest first.
+ *   - Return value: MOE_OK (0) or a negative moe_status.  Argument errors are
+ *     found on the host before anything is enqueued and leave outputs untouched.
+ *   - Routed rows: P = T*K.  A routed row has a flat id f = t*K + j (token t,
+ *     slot j) and a sorted position p in [0,P): rows are sorted by expert id,
+ *     and by ascending flat id inside one expert's group.
+ *   - NaN/Inf inputs are not supported (results undefined, no fault).
+ *   - T = 0 is a valid call: buffers that have a T (or P) dimension may then be NULL; counts
+ *     and offsets are still written (all zero).
+ */
+#ifndef MOE_PREFILL_H
+#define MOE_PREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_ABI_VERSION 1
+
+typedef enum moe_status {
+    MOE_OK = 0,
+    MOE_ERR_NULL_PTR = -1,
+    MOE_ERR_BAD_SHAPE = -2,
+    MOE_ERR_BAD_DTYPE = -3,
+    MOE_ERR_UNALIGNED = -4,
+    MOE_ERR_WORKSPACE_TOO_SMALL = -5,
+    MOE_ERR_UNSUPPORTED = -6,
+    MOE_ERR_LAUNCH_FAILED = -7
+} moe_status;
+
+typedef enum moe_dtype {
+    MOE_DTYPE_F32 = 0,
+    MOE_DTYPE_BF16 = 1,
+    MOE_DTYPE_FP8_E4M3 = 2 /* OCP e4m3 (finite max 448, no infinities) */
+} moe_dtype;
+
+enum { /* moe_config.flags */
+    MOE_FLAG_NONE = 0
+};
+
+typedef enum moe_call {
+    MOE_CALL_ROUTE = 0,
+    MOE_CALL_PERMUTE = 1,
+    MOE_CALL_GROUPED_FFN = 2,
+    MOE_CALL_COMBINE = 3,
+    MOE_CALL_PREFILL_LAYER = 4
+} moe_call;
+
+/* Shape and types of one layer call.
+ *   T tokens, H hidden size, E experts, K experts per token, I expert
+ *   intermediate size.  Limits: 1 <= K <= min(E, 32), E <= 1024, T*K < 2^31,
+ *   T >= 0 (T = 0 is a valid no-op).
+ *   x_dtype   F32 or BF16                       (activations x)
+ *   w_dtype   F32 (needs x F32), BF16 (needs x BF16) or FP8_E4M3 (needs x BF16;
+ *             weights are e4m3 codes with one float scale per output channel)
+ *   out_dtype F32 or BF16 (the bf16 result is the float32 result rounded once)
+ *   BF16/FP8 paths need H % 64 == 0 and I % 64 == 0; the F32 path takes any size.
+ */
+typedef struct moe_config {
+    int32_t T, H, E, K, I;
+    int32_t x_dtype;
+    int32_t w_dtype;
+    int32_t out_dtype;
+    int32_t flags;
+} moe_config_t;
+
+/* Optional intermediate outputs of moe_prefill_layer (any member may be NULL).
+ * Shapes as in the single calls below. */
+typedef struct moe_taps {
+    float *logits;       /* [T,E]   */
+    int32_t *topk_idx;   /* [T,K]   */
+    float *topk_w;       /* [T,K]   */
+    int32_t *counts;     /* [E]     */
+    int32_t *offsets;    /* [E+1]   */
+    int32_t *perm;       /* [P]     */
+    int32_t *inv_perm;   /* [P]     */
+    void *act;           /* [P,I]   SwiGLU activations in sorted row order: F32 for the F32 path, else BF16 */
+    uint8_t *act_q;      /* [P,I]   FP8 path only: e4m3 codes of act            */
+    float *act_scale;    /* [P]     FP8 path only: per-row scales of act        */
+    float *y_perm;       /* [P,H]   expert outputs in sorted row order, F32     */
+} moe_taps_t;
+
+int32_t moe_abi_version(void);
+const char *moe_status_string(int32_t status);
+
+/* Minimum workspace, in bytes, of one entry point for this config. */
+int32_t moe_workspace_bytes(const moe_config_t *cfg, int32_t call, size_t *bytes_out);
+
+/* Per-row e4m3 quantiser, the fp8 storage of expert weights (rows = output
+ * channels) and of activations (rows = tokens), for the FP8 precision the paper
+ * deploys (Sec. 8.1).  All steps in IEEE binary32:
+ *   scale[r] = max_c |src[r,c]| / 448  (1 if the row is all zero)
+ *   q[r,c]   = e4m3(src[r,c] / scale[r]), round to nearest even, saturating.
+ * src is BF16 [rows, cols], cols % 8 == 0; q is [rows, cols] bytes; scale [rows]. */
+int32_t moe_quantize_rows_e4m3(const void *src_bf16, int64_t rows, int32_t cols, uint8_t *q,
+                               float *scale, void *stream);
+
+/* Router (Sec. 2.3, "a lightweight router dispatches each token to its top-k
+ * experts").  logits[t,e] = sum_h x[t,h]*w_router[e,h] (+ bias[e]), accumulated in
+ * float32; per token the K largest logits in descending order, equal values
+ * ordered by ascending expert index; topk_w = softmax over the selected logits
+ * (equal to the full softmax renormalised over the selection).
+ *   x [T,H] (x_dtype), w_router [E,H] F32, bias [E] F32 or NULL,
+ *   logits_out [T,E] F32 or NULL (then T*E floats of ws are used),
+ *   topk_idx [T,K] int32, topk_w [T,K] F32. */
+int32_t moe_route(const moe_config_t *cfg, const void *x, const float *w_router, const float *bias,
+                  float *logits_out, int32_t *topk_idx, float *topk_w, void *ws, size_t ws_bytes,
+                  void *stream);
+
+/* Grouping by expert (the token permutation/alignment step of Sec. 4.3).
+ *   counts[e] = number of routed rows of expert e; offsets = exclusive prefix sum,
+ *   offsets[E] = P; perm[p] = flat id of sorted row p; inv_perm[f] = sorted position
+ *   of flat id f.  Deterministic, independent of scheduling.
+ *   x, x_perm: optional; when both are given x_perm[p,:] = x[perm[p]/K,:]
+ *   ([P,H], x_dtype).  moe_grouped_ffn does not need x_perm (it gathers rows
+ *   itself). */
+int32_t moe_permute(const moe_config_t *cfg, const int32_t *topk_idx, const void *x, int32_t *counts,
+                    int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/* Grouped SwiGLU expert FFN over the ragged per-expert row groups (the per-expert
+ * GEMMs of Sec. 4.2).  For sorted row p in expert e's group, with
+ * x_p = x[perm[p]/K,:]:
+ *   g = Wg_e x_p, u = Wu_e x_p, a = g/(1+exp(-g))*u, y_perm[p,:] = Wd_e a.
+ * Accumulation is float32; a is rounded once to BF16 between the two GEMMs
+ * (kept F32 on the F32 path).  FP8 path: x rows and a rows are quantised per
+ * row as in moe_quantize_rows_e4m3 and the float scales are applied to the
+ * float32 accumulators.
+ *   x [T,H]; perm [P]; offsets [E+1]; w_gate,w_up [E,I,H]; w_down [E,H,I]
+ *   (w_dtype; FP8: bytes); s_gate,s_up [E,I], s_down [E,H] F32 (FP8 only, else
+ *   NULL); act_tap [P,I] or NULL (BF16, F32 on the F32 path); act_q_tap [P,I],
+ *   act_scale_tap [P] or NULL (FP8 only); y_perm [P,H] F32. */
+int32_t moe_grouped_ffn(const moe_config_t *cfg, const void *x, const int32_t *perm,
+                        const int32_t *offsets, const void *w_gate, const void *w_up,
+                        const void *w_down, const float *s_gate, const float *s_up,
+                        const float *s_down, void *act_tap, uint8_t *act_q_tap,
+                        float *act_scale_tap, float *y_perm, void *ws, size_t ws_bytes,
+                        void *stream);
+
+/* Weighted combine back to token order ("sums their outputs", Sec. 2.3):
+ *   out[t,:] = sum_{j<K} topk_w[t,j] * y_perm[inv_perm[t*K+j],:], float32 FMA in
+ *   slot order, one rounding to out_dtype.  out [T,H]. */
+int32_t moe_combine(const moe_config_t *cfg, const float *y_perm, const int32_t *inv_perm,
+                    const float *topk_w, void *out, void *stream);
+
+/* The whole block in one call; bit-identical to the four calls above in sequence.
+ * taps may be NULL. */
+int32_t moe_prefill_layer(const moe_config_t *cfg, const void *x, const float *w_router,
+                          const float *bias, const void *w_gate, const void *w_up,
+                          const void *w_down, const float *s_gate, const float *s_up,
+                          const float *s_down, void *out, const moe_taps_t *taps, void *ws,
+                          size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_PREFILL_H */

@@ -123,6 +123,11 @@ def expert_ffn_rows(xe, wg, wu, wd, act_rounding="none", fp8=False, taps=None):
     return a @ wd.T
 
 
+def down_project(act_rows, w_down, e, fp8=False):
+    """Second expert GEMM alone: y = Wd_e a for given activations a [m,I] (float64 values)."""
+    return np.asarray(act_rows, dtype=np.float64) @ _expert_weights_f64(w_down, e, fp8).T
+
+
 # ------------------------------------------------------------------ the layer
 def moe_layer(x, w_router, w_gate, w_up, w_down, k, bias=None, *,
               act_rounding="none", fp8=False, tokens=None, routing_logits=None,

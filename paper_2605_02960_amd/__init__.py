@@ -1,0 +1,12 @@
+"""MI355X-native MoE prefill block (router, top-k, grouping, grouped SwiGLU expert FFN,
+combine) behind a C ABI; see include/moe_prefill.h.  This package is the thin Python
+binding: it marshals torch device tensors into the library's entry points and does no
+arithmetic of its own.  Importing it does not load the library; the first call does, and
+raises if libmoeprefill.so has not been built (python -m paper_2605_02960_amd.build)."""
+from .binding import (  # noqa: F401
+    MoEConfig, MoETaps, MoEError, DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3,
+    CALL_ROUTE, CALL_PERMUTE, CALL_GROUPED_FFN, CALL_COMBINE, CALL_PREFILL_LAYER,
+    lib, lib_path, moe_abi_version, moe_status_string, moe_workspace_bytes,
+    moe_quantize_rows_e4m3, moe_route, moe_permute, moe_grouped_ffn, moe_combine,
+    moe_prefill_layer, make_config, EXPORTED_SYMBOLS,
+)

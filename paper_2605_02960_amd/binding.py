@@ -1,0 +1,203 @@
+"""ctypes binding of libmoeprefill.so.  Argument marshalling only: every tensor is a torch
+tensor on the GPU (torch is used for device memory and streams), every step of the block
+runs inside the library's HIP kernels."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmoeprefill.so")
+_lib = None
+
+DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3 = 0, 1, 2
+CALL_ROUTE, CALL_PERMUTE, CALL_GROUPED_FFN, CALL_COMBINE, CALL_PREFILL_LAYER = range(5)
+
+EXPORTED_SYMBOLS = (
+    "moe_abi_version", "moe_status_string", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
+    "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
+)
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {moe_status_string(status)} ({status})")
+
+
+class MoEConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "H", "E", "K", "I", "x_dtype", "w_dtype", "out_dtype", "flags")]
+
+
+class MoETaps(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv_perm", "act",
+                 "act_q", "act_scale", "y_perm")]
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2605_02960_amd.build` (hipcc, gfx950)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        cfgp = ctypes.POINTER(MoEConfig)
+        L.moe_abi_version.restype = i32
+        L.moe_abi_version.argtypes = []
+        L.moe_status_string.restype = ctypes.c_char_p
+        L.moe_status_string.argtypes = [i32]
+        L.moe_workspace_bytes.restype = i32
+        L.moe_workspace_bytes.argtypes = [cfgp, i32, ctypes.POINTER(sz)]
+        L.moe_quantize_rows_e4m3.restype = i32
+        L.moe_quantize_rows_e4m3.argtypes = [vp, i64, i32, vp, vp, vp]
+        L.moe_route.restype = i32
+        L.moe_route.argtypes = [cfgp] + [vp] * 7 + [sz, vp]
+        L.moe_permute.restype = i32
+        L.moe_permute.argtypes = [cfgp] + [vp] * 8 + [sz, vp]
+        L.moe_grouped_ffn.restype = i32
+        L.moe_grouped_ffn.argtypes = [cfgp] + [vp] * 14 + [sz, vp]
+        L.moe_combine.restype = i32
+        L.moe_combine.argtypes = [cfgp] + [vp] * 5
+        L.moe_prefill_layer.restype = i32
+        L.moe_prefill_layer.argtypes = [cfgp] + [vp] * 10 + [ctypes.POINTER(MoETaps), vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+# ------------------------------------------------------------------ helpers
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(st, where):
+    if st != 0:
+        raise MoEError(st, where)
+
+
+def _ws(cfg, call, device):
+    n = moe_workspace_bytes(cfg, call)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device), n
+
+
+_TORCH_OF = {DTYPE_F32: torch.float32, DTYPE_BF16: torch.bfloat16}
+
+
+def make_config(T, H, E, K, I, x_dtype, w_dtype, out_dtype=DTYPE_F32, flags=0):
+    return MoEConfig(T, H, E, K, I, x_dtype, w_dtype, out_dtype, flags)
+
+
+# ------------------------------------------------------------------ entry points
+def moe_abi_version():
+    return lib().moe_abi_version()
+
+
+def moe_status_string(status):
+    return lib().moe_status_string(status).decode()
+
+
+def moe_workspace_bytes(cfg, call):
+    n = ctypes.c_size_t(0)
+    _check(lib().moe_workspace_bytes(ctypes.byref(cfg), call, ctypes.byref(n)), "moe_workspace_bytes")
+    return n.value
+
+
+def moe_quantize_rows_e4m3(src_bf16, stream=None):
+    """src [rows, cols] bf16 -> (codes uint8 [rows, cols], scale float32 [rows])."""
+    rows, cols = src_bf16.shape
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=src_bf16.device)
+    s = torch.empty((rows,), dtype=torch.float32, device=src_bf16.device)
+    _check(lib().moe_quantize_rows_e4m3(_p(src_bf16), rows, cols, _p(q), _p(s), _stream(stream)),
+           "moe_quantize_rows_e4m3")
+    return q, s
+
+
+def moe_route(cfg, x, w_router, bias=None, want_logits=True, stream=None):
+    dev = x.device
+    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device=dev)
+    w = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device=dev)
+    logits = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device=dev) if want_logits else None
+    ws, n = (None, 0) if want_logits else _ws(cfg, CALL_ROUTE, dev)
+    _check(lib().moe_route(ctypes.byref(cfg), _p(x), _p(w_router), _p(bias), _p(logits), _p(idx), _p(w),
+                           _p(ws), n, _stream(stream)), "moe_route")
+    return idx, w, logits
+
+
+def moe_permute(cfg, topk_idx, x=None, want_x_perm=False, stream=None):
+    dev = topk_idx.device
+    P = cfg.T * cfg.K
+    counts = torch.empty((cfg.E,), dtype=torch.int32, device=dev)
+    offsets = torch.empty((cfg.E + 1,), dtype=torch.int32, device=dev)
+    perm = torch.empty((P,), dtype=torch.int32, device=dev)
+    inv = torch.empty((P,), dtype=torch.int32, device=dev)
+    xp = torch.empty((P, cfg.H), dtype=x.dtype, device=dev) if want_x_perm else None
+    ws, n = _ws(cfg, CALL_PERMUTE, dev)
+    _check(lib().moe_permute(ctypes.byref(cfg), _p(topk_idx), _p(x), _p(counts), _p(offsets), _p(perm),
+                             _p(inv), _p(xp), _p(ws), n, _stream(stream)), "moe_permute")
+    return counts, offsets, perm, inv, xp
+
+
+def moe_grouped_ffn(cfg, x, perm, offsets, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down=None,
+                    want_act=False, y_perm=None, ws=None, stream=None):
+    dev = x.device
+    P = cfg.T * cfg.K
+    fp8 = cfg.w_dtype == DTYPE_FP8_E4M3
+    act = act_q = act_s = None
+    if want_act:
+        act = torch.empty((P, cfg.I), dtype=torch.float32 if cfg.w_dtype == DTYPE_F32 else torch.bfloat16,
+                          device=dev)
+        if fp8:
+            act_q = torch.empty((P, cfg.I), dtype=torch.uint8, device=dev)
+            act_s = torch.empty((P,), dtype=torch.float32, device=dev)
+    if y_perm is None:
+        y_perm = torch.empty((P, cfg.H), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws, n = _ws(cfg, CALL_GROUPED_FFN, dev)
+    else:
+        n = ws.numel()
+    _check(lib().moe_grouped_ffn(ctypes.byref(cfg), _p(x), _p(perm), _p(offsets), _p(w_gate), _p(w_up),
+                                 _p(w_down), _p(s_gate), _p(s_up), _p(s_down), _p(act), _p(act_q),
+                                 _p(act_s), _p(y_perm), _p(ws), n, _stream(stream)), "moe_grouped_ffn")
+    return y_perm, act, act_q, act_s
+
+
+def moe_combine(cfg, y_perm, inv_perm, topk_w, out=None, stream=None):
+    if out is None:
+        out = torch.empty((cfg.T, cfg.H), dtype=_TORCH_OF[cfg.out_dtype], device=y_perm.device)
+    _check(lib().moe_combine(ctypes.byref(cfg), _p(y_perm), _p(inv_perm), _p(topk_w), _p(out),
+                             _stream(stream)), "moe_combine")
+    return out
+
+
+def moe_prefill_layer(cfg, x, w_router, bias, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down=None,
+                      out=None, taps=None, ws=None, stream=None):
+    """taps: None, or a dict name -> preallocated tensor for any of the MoETaps members."""
+    dev = x.device
+    if out is None:
+        out = torch.empty((cfg.T, cfg.H), dtype=_TORCH_OF[cfg.out_dtype], device=dev)
+    if ws is None:
+        ws, n = _ws(cfg, CALL_PREFILL_LAYER, dev)
+    else:
+        n = ws.numel()
+    tp = None
+    if taps:
+        t = MoETaps()
+        for name, ten in taps.items():
+            setattr(t, name, ten.data_ptr())
+        tp = ctypes.byref(t)
+    _check(lib().moe_prefill_layer(ctypes.byref(cfg), _p(x), _p(w_router), _p(bias), _p(w_gate), _p(w_up),
+                                   _p(w_down), _p(s_gate), _p(s_up), _p(s_down), _p(out), tp, _p(ws), n,
+                                   _stream(stream)), "moe_prefill_layer")
+    return out

@@ -1,0 +1,77 @@
+// Weighted combine back to token order: out[t,:] = sum_j w[t,j] * y_perm[inv_perm[t*K+j],:]
+// ("sums their outputs", Sec. 2.3 of the paper).  HBM-bound gather-reduce: every y_perm row is
+// read exactly once, 16 bytes per lane, and the K terms are added in slot order in float32, so
+// the result is deterministic.
+#include "common.h"
+
+namespace moe {
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__ y, int row_vec,
+                                                     const int32_t* __restrict__ inv_perm,
+                                                     const float* __restrict__ w, int K,
+                                                     void* __restrict__ out) {
+    __shared__ int32_t pos[32];
+    __shared__ float wt[32];
+    const int t = blockIdx.x;
+    if (threadIdx.x < K) {
+        pos[threadIdx.x] = inv_perm[(size_t)t * K + threadIdx.x];
+        wt[threadIdx.x] = w[(size_t)t * K + threadIdx.x];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < row_vec; i += blockDim.x) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < K; ++j) {
+            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(y + (size_t)pos[j] * row_vec + i));
+            const float s = wt[j];
+            acc.x = fmaf(s, v.x, acc.x);
+            acc.y = fmaf(s, v.y, acc.y);
+            acc.z = fmaf(s, v.z, acc.z);
+            acc.w = fmaf(s, v.w, acc.w);
+        }
+        if constexpr (OUT_BF16) {
+            uint2 o;
+            o.x = (uint32_t)f32_to_bf16_bits(acc.x) | ((uint32_t)f32_to_bf16_bits(acc.y) << 16);
+            o.y = (uint32_t)f32_to_bf16_bits(acc.z) | ((uint32_t)f32_to_bf16_bits(acc.w) << 16);
+            static_cast<uint2*>(out)[(size_t)t * row_vec + i] = o;
+        } else {
+            static_cast<float4*>(out)[(size_t)t * row_vec + i] = acc;
+        }
+    }
+}
+
+// Any H (no vector width assumption).
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void combine_scalar_kernel(const float* __restrict__ y, int H,
+                                                            const int32_t* __restrict__ inv_perm,
+                                                            const float* __restrict__ w, int K,
+                                                            void* __restrict__ out) {
+    const int t = blockIdx.x;
+    for (int h = threadIdx.x; h < H; h += blockDim.x) {
+        float acc = 0.f;
+        for (int j = 0; j < K; ++j)
+            acc = fmaf(w[(size_t)t * K + j], y[(size_t)inv_perm[(size_t)t * K + j] * H + h], acc);
+        if constexpr (OUT_BF16)
+            static_cast<uint16_t*>(out)[(size_t)t * H + h] = f32_to_bf16_bits(acc);
+        else
+            static_cast<float*>(out)[(size_t)t * H + h] = acc;
+    }
+}
+
+int32_t launch_combine(const moe_config_t& c, const float* y_perm, const int32_t* inv_perm,
+                       const float* topk_w, void* out, hipStream_t s) {
+    if (c.T == 0) return MOE_OK;
+    const bool bf = c.out_dtype == MOE_DTYPE_BF16;
+    const bool vec = (c.H % 4 == 0) && ((uintptr_t)y_perm % 16 == 0) && ((uintptr_t)out % 16 == 0);
+    if (vec) {
+        const float4* y = reinterpret_cast<const float4*>(y_perm);
+        if (bf) combine_kernel<true><<<c.T, 256, 0, s>>>(y, c.H / 4, inv_perm, topk_w, c.K, out);
+        else combine_kernel<false><<<c.T, 256, 0, s>>>(y, c.H / 4, inv_perm, topk_w, c.K, out);
+    } else {
+        if (bf) combine_scalar_kernel<true><<<c.T, 256, 0, s>>>(y_perm, c.H, inv_perm, topk_w, c.K, out);
+        else combine_scalar_kernel<false><<<c.T, 256, 0, s>>>(y_perm, c.H, inv_perm, topk_w, c.K, out);
+    }
+    return launch_status();
+}
+
+}  // namespace moe

@@ -1,0 +1,82 @@
+// Internal declarations shared by the HIP sources of libmoeprefill (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/moe_prefill.h"
+
+namespace moe {
+
+constexpr int WAVE = 64;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// bf16 <-> f32 on raw bit patterns (round to nearest even; inputs are finite).
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+__host__ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline int32_t launch_status() {
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH_FAILED;
+}
+
+// ---- route.hip
+// logits [T,E] f32 = x [T,H] (f32 or bf16 bits) . w_router[E,H]^T (+bias); then top-k.
+int32_t launch_router_logits(const moe_config_t& c, const void* x, const float* w_router,
+                             const float* bias, float* logits, hipStream_t s);
+int32_t launch_topk(const moe_config_t& c, const float* logits, int32_t* topk_idx, float* topk_w,
+                    hipStream_t s);
+
+// ---- permute.hip
+size_t permute_ws_bytes(const moe_config_t& c);
+int32_t launch_permute(const moe_config_t& c, const int32_t* topk_idx, int32_t* counts,
+                       int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t s);
+int32_t launch_gather_rows(const moe_config_t& c, const void* x, const int32_t* perm, void* x_perm,
+                           hipStream_t s);
+
+// ---- tiles.hip : per-expert row tiles of height bm, built on the device from offsets.
+// table[0] = number of tiles n; table[1 + 2*i] = expert, table[2 + 2*i] = first sorted row of tile i.
+inline int64_t max_row_tiles(const moe_config_t& c, int bm) {
+    return ((int64_t)c.T * c.K) / bm + c.E;
+}
+inline size_t tile_table_bytes(const moe_config_t& c, int bm) {
+    return align_up(sizeof(int32_t) * (1 + 2 * (size_t)max_row_tiles(c, bm)), 256);
+}
+int32_t launch_build_tile_table(const moe_config_t& c, const int32_t* offsets, int bm,
+                                int32_t* table, hipStream_t s);
+
+// ---- ffn_f32.hip
+size_t ffn_f32_ws_bytes(const moe_config_t& c);
+int32_t launch_ffn_f32(const moe_config_t& c, const float* x, const int32_t* perm,
+                       const int32_t* offsets, const float* wg, const float* wu, const float* wd,
+                       float* act_tap, float* y_perm, void* ws, hipStream_t s);
+
+// ---- ffn_mfma.hip (bf16 and fp8)
+size_t ffn_mfma_ws_bytes(const moe_config_t& c);
+int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* wg, const void* wu, const void* wd,
+                        const float* s_gate, const float* s_up, const float* s_down, void* act_tap,
+                        uint8_t* act_q_tap, float* act_scale_tap, float* y_perm, void* ws,
+                        hipStream_t s);
+
+// ---- combine.hip
+int32_t launch_combine(const moe_config_t& c, const float* y_perm, const int32_t* inv_perm,
+                       const float* topk_w, void* out, hipStream_t s);
+
+// ---- quant.hip
+int32_t launch_quantize_rows(const void* src_bf16, int64_t rows, int32_t cols, uint8_t* q,
+                             float* scale, hipStream_t s);
+
+}  // namespace moe

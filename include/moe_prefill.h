@@ -102,11 +102,30 @@ typedef struct moe_taps {
     float *y_perm;       /* [P,H]   expert outputs in sorted row order, F32     */
 } moe_taps_t;
 
+/* Kernels that moe_set_profile_events can bracket. */
+typedef enum moe_kernel {
+    MOE_KERNEL_ROUTER_GEMM = 0,
+    MOE_KERNEL_TOPK = 1,
+    MOE_KERNEL_PERMUTE = 2,   /* histogram + scan + scatter (three launches) */
+    MOE_KERNEL_GATE_UP = 3,   /* grouped gate/up GEMM with the SwiGLU epilogue */
+    MOE_KERNEL_DOWN = 4,      /* grouped down GEMM */
+    MOE_KERNEL_COMBINE = 5,
+    MOE_KERNEL_COUNT = 6
+} moe_kernel;
+
 int32_t moe_abi_version(void);
 const char *moe_status_string(int32_t status);
 
 /* Minimum workspace, in bytes, of one entry point for this config. */
 int32_t moe_workspace_bytes(const moe_config_t *cfg, int32_t call, size_t *bytes_out);
+
+/* Measurement hook (Sec. 8.5 of the paper reports utilisation as achieved over peak FLOP/s;
+ * this is how one kernel's share is timed without a profiler).  While a (start, stop) pair of
+ * hipEvent_t (passed as void*, created by the caller with timing enabled) is set for a kernel,
+ * every launch of that kernel is bracketed by hipEventRecord(start, stream) and
+ * hipEventRecord(stop, stream).  Pass NULL, NULL to clear.  Host-side state of the calling
+ * process, not thread-safe; costs nothing when unset. */
+int32_t moe_set_profile_events(int32_t kernel, void *start_event, void *stop_event);
 
 /* Per-row e4m3 quantiser, the fp8 storage of expert weights (rows = output
  * channels) and of activations (rows = tokens), for the FP8 precision the paper

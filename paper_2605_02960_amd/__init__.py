@@ -6,6 +6,8 @@ raises if libmoeprefill.so has not been built (python -m paper_2605_02960_amd.bu
 from .binding import (  # noqa: F401
     MoEConfig, MoETaps, MoEError, DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3,
     CALL_ROUTE, CALL_PERMUTE, CALL_GROUPED_FFN, CALL_COMBINE, CALL_PREFILL_LAYER,
+    KERNEL_ROUTER_GEMM, KERNEL_TOPK, KERNEL_PERMUTE, KERNEL_GATE_UP, KERNEL_DOWN, KERNEL_COMBINE,
+    KERNEL_NAMES, moe_set_profile_events,
     lib, lib_path, moe_abi_version, moe_status_string, moe_workspace_bytes,
     moe_quantize_rows_e4m3, moe_route, moe_permute, moe_grouped_ffn, moe_combine,
     moe_prefill_layer, make_config, EXPORTED_SYMBOLS,

@@ -13,8 +13,11 @@ _lib = None
 DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3 = 0, 1, 2
 CALL_ROUTE, CALL_PERMUTE, CALL_GROUPED_FFN, CALL_COMBINE, CALL_PREFILL_LAYER = range(5)
 
+KERNEL_ROUTER_GEMM, KERNEL_TOPK, KERNEL_PERMUTE, KERNEL_GATE_UP, KERNEL_DOWN, KERNEL_COMBINE = range(6)
+KERNEL_NAMES = ("router_gemm", "topk", "permute", "gate_up", "down", "combine")
+
 EXPORTED_SYMBOLS = (
-    "moe_abi_version", "moe_status_string", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
+    "moe_abi_version", "moe_status_string", "moe_set_profile_events", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
 )
 
@@ -54,6 +57,8 @@ def lib():
         L.moe_abi_version.argtypes = []
         L.moe_status_string.restype = ctypes.c_char_p
         L.moe_status_string.argtypes = [i32]
+        L.moe_set_profile_events.restype = i32
+        L.moe_set_profile_events.argtypes = [i32, vp, vp]
         L.moe_workspace_bytes.restype = i32
         L.moe_workspace_bytes.argtypes = [cfgp, i32, ctypes.POINTER(sz)]
         L.moe_quantize_rows_e4m3.restype = i32
@@ -106,6 +111,13 @@ def moe_abi_version():
 
 def moe_status_string(status):
     return lib().moe_status_string(status).decode()
+
+
+def moe_set_profile_events(kernel, start_event, stop_event):
+    """start_event / stop_event: raw hipEvent_t handles (int) or None to clear."""
+    _check(lib().moe_set_profile_events(kernel, ctypes.c_void_p(start_event) if start_event else None,
+                                        ctypes.c_void_p(stop_event) if stop_event else None),
+           "moe_set_profile_events")
 
 
 def moe_workspace_bytes(cfg, call):

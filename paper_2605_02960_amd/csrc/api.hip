@@ -4,6 +4,10 @@
 
 using namespace moe;
 
+namespace moe {
+ProfileSlot g_profile[MOE_KERNEL_COUNT] = {};
+}
+
 namespace {
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -78,6 +82,14 @@ const char* moe_status_string(int32_t st) {
         case MOE_ERR_LAUNCH_FAILED: return "kernel launch failed";
         default: return "unknown status";
     }
+}
+
+int32_t moe_set_profile_events(int32_t kernel, void* start_event, void* stop_event) {
+    if (kernel < 0 || kernel >= MOE_KERNEL_COUNT) return MOE_ERR_UNSUPPORTED;
+    if ((start_event == nullptr) != (stop_event == nullptr)) return MOE_ERR_NULL_PTR;
+    g_profile[kernel].start = static_cast<hipEvent_t>(start_event);
+    g_profile[kernel].stop = static_cast<hipEvent_t>(stop_event);
+    return MOE_OK;
 }
 
 int32_t moe_workspace_bytes(const moe_config_t* cfg, int32_t call, size_t* bytes_out) {

@@ -62,6 +62,7 @@ int32_t launch_combine(const moe_config_t& c, const float* y_perm, const int32_t
                        const float* topk_w, void* out, hipStream_t s) {
     if (c.T == 0) return MOE_OK;
     const bool bf = c.out_dtype == MOE_DTYPE_BF16;
+    KernelBracket kb(MOE_KERNEL_COMBINE, s);
     const bool vec = (c.H % 4 == 0) && ((uintptr_t)y_perm % 16 == 0) && ((uintptr_t)out % 16 == 0);
     if (vec) {
         const float4* y = reinterpret_cast<const float4*>(y_perm);

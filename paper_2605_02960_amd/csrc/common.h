@@ -13,6 +13,7 @@ constexpr int WAVE = 64;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // bf16 <-> f32 on raw bit patterns (round to nearest even; inputs are finite).
@@ -31,6 +32,22 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int32_t launch_status() {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH_FAILED;
 }
+
+// Optional per-kernel event bracket (see moe_set_profile_events).
+struct ProfileSlot {
+    hipEvent_t start, stop;
+};
+extern ProfileSlot g_profile[MOE_KERNEL_COUNT];
+struct KernelBracket {
+    const ProfileSlot& p;
+    hipStream_t s;
+    KernelBracket(int kernel, hipStream_t stream) : p(g_profile[kernel]), s(stream) {
+        if (p.start) (void)hipEventRecord(p.start, s);
+    }
+    ~KernelBracket() {
+        if (p.stop) (void)hipEventRecord(p.stop, s);
+    }
+};
 
 // ---- route.hip
 // logits [T,E] f32 = x [T,H] (f32 or bf16 bits) . w_router[E,H]^T (+bias); then top-k.

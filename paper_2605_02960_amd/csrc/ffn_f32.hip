@@ -39,8 +39,11 @@ int32_t launch_ffn_f32(const moe_config_t& c, const float* x, const int32_t* per
     a.bias = nullptr;
     a.C = act;
     a.ldc = c.I;
-    f32_gemm_nt_kernel<float, 64, 64, 4, 4, EPI_SWIGLU>
-        <<<dim3(tiles, (unsigned)ceil_div64(c.I, 64)), 256, 0, s>>>(a);
+    {
+        KernelBracket kb(MOE_KERNEL_GATE_UP, s);
+        f32_gemm_nt_kernel<float, 64, 64, 4, 4, EPI_SWIGLU>
+            <<<dim3(tiles, (unsigned)ceil_div64(c.I, 64)), 256, 0, s>>>(a);
+    }
 
     F32GemmArgs b{};
     b.A = act;
@@ -57,8 +60,11 @@ int32_t launch_ffn_f32(const moe_config_t& c, const float* x, const int32_t* per
     b.bias = nullptr;
     b.C = y_perm;
     b.ldc = c.H;
-    f32_gemm_nt_kernel<float, 64, 64, 4, 4, EPI_STORE>
-        <<<dim3(tiles, (unsigned)ceil_div64(c.H, 64)), 256, 0, s>>>(b);
+    {
+        KernelBracket kb(MOE_KERNEL_DOWN, s);
+        f32_gemm_nt_kernel<float, 64, 64, 4, 4, EPI_STORE>
+            <<<dim3(tiles, (unsigned)ceil_div64(c.H, 64)), 256, 0, s>>>(b);
+    }
     return launch_status();
 }
 

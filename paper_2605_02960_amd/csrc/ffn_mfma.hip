@@ -117,21 +117,23 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nj][mi][v] = 0.f;
 
-    uint4 ra[4], rb[4];
-#define MOE_GLOAD(KT_)                                                                    \
+    // Two register sets of staged global loads: the tile for K step kt+2 is requested while step
+    // kt is being multiplied, so every request has two K steps of MFMA work to hide its latency.
+    u32x4 ra0[4], rb0[4], ra1[4], rb1[4];
+#define MOE_GLOAD(SET_, KT_)                                                              \
     {                                                                                     \
-        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                  \
+        const uint32_t kb = (uint32_t)min((KT_), KT - 1) * ROW_BYTES;                     \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                   \
-            ra[i] = *reinterpret_cast<const uint4*>(a.A + (a_off[i] + kb));               \
-            rb[i] = *reinterpret_cast<const uint4*>(((i < 2 || MODE == MODE_DOWN) ? b0e : b1e) + (b_off[i] + kb)); \
+            ra##SET_[i] = *reinterpret_cast<const u32x4*>(a.A + (a_off[i] + kb));         \
+            rb##SET_[i] = *reinterpret_cast<const u32x4*>(((i < 2 || MODE == MODE_DOWN) ? b0e : b1e) + (b_off[i] + kb)); \
         }                                                                                 \
     }
-#define MOE_LSTORE(STAGE_)                                                                \
+#define MOE_LSTORE(SET_, STAGE_)                                                          \
     {                                                                                     \
         char* base = smem + (STAGE_) * STAGE_BYTES + st_off;                              \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                   \
-            *reinterpret_cast<uint4*>(base + i * 64 * ROW_BYTES) = ra[i];                 \
-            *reinterpret_cast<uint4*>(base + TILE_BYTES + i * 64 * ROW_BYTES) = rb[i];    \
+            *reinterpret_cast<u32x4*>(base + i * 64 * ROW_BYTES) = ra##SET_[i];           \
+            *reinterpret_cast<u32x4*>(base + TILE_BYTES + i * 64 * ROW_BYTES) = rb##SET_[i]; \
         }                                                                                 \
     }
 #define MOE_COMPUTE(STAGE_)                                                               \
@@ -150,16 +152,22 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
 
     const int KT = a.Kd / BK;
-    MOE_GLOAD(0);
-    MOE_LSTORE(0);
+    MOE_GLOAD(0, 0);
+    MOE_GLOAD(1, 1);
+    MOE_LSTORE(0, 0);
     __syncthreads();
-    for (int kt = 0; kt < KT - 1; ++kt) {
-        MOE_GLOAD(kt + 1);
-        MOE_COMPUTE(kt & 1);
-        MOE_LSTORE((kt + 1) & 1);
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+        MOE_GLOAD(0, kt + 2);
+        MOE_COMPUTE(0);
+        MOE_LSTORE(1, 1);
+        __syncthreads();
+        MOE_GLOAD(1, kt + 3);
+        MOE_COMPUTE(1);
+        MOE_LSTORE(0, 0);
         __syncthreads();
     }
-    MOE_COMPUTE((KT - 1) & 1);
+    if (kt < KT) MOE_COMPUTE(0);
 #undef MOE_GLOAD
 #undef MOE_LSTORE
 #undef MOE_COMPUTE
@@ -255,6 +263,7 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     g.nct = (int32_t)ceil_div64(c.I, 128);
     {
         const int64_t grid = ceil_div64(mrt * g.nct, 8) * 8;
+        KernelBracket kb(MOE_KERNEL_GATE_UP, s);
         ffn_mfma_kernel<MODE_GATE_UP><<<(unsigned)grid, THREADS, 2 * STAGE_BYTES, s>>>(g);
     }
     MfmaArgs d{};
@@ -272,6 +281,7 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.nct = (int32_t)ceil_div64(c.H, 256);
     {
         const int64_t grid = ceil_div64(mrt * d.nct, 8) * 8;
+        KernelBracket kb(MOE_KERNEL_DOWN, s);
         ffn_mfma_kernel<MODE_DOWN><<<(unsigned)grid, THREADS, 2 * STAGE_BYTES, s>>>(d);
     }
     return launch_status();

@@ -139,6 +139,7 @@ int32_t launch_permute(const moe_config_t& c, const int32_t* topk_idx, int32_t* 
     const int64_t P = (int64_t)c.T * c.K;
     const int nseg = (int)ceil_div64(P, SEG);
     int32_t* seg = static_cast<int32_t*>(ws);
+    KernelBracket kb(MOE_KERNEL_PERMUTE, s);
     if (nseg > 0) seg_hist_kernel<<<nseg, PERM_THREADS, 0, s>>>(topk_idx, (int)P, c.E, seg);
     seg_scan_kernel<<<1, 1024, 0, s>>>(seg, nseg, c.E, counts, offsets);
     if (nseg > 0)

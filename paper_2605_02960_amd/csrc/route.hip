@@ -22,6 +22,7 @@ int32_t launch_router_logits(const moe_config_t& c, const void* x, const float* 
     a.bias = bias;
     a.C = logits;
     a.ldc = c.E;
+    KernelBracket kb(MOE_KERNEL_ROUTER_GEMM, s);
     if (c.E > 64) {
         dim3 grid((unsigned)ceil_div64(c.T, 128), (unsigned)ceil_div64(c.E, 128));
         if (c.x_dtype == MOE_DTYPE_F32)
@@ -110,6 +111,7 @@ int32_t launch_topk(const moe_config_t& c, const float* logits, int32_t* topk_id
     const int waves_per_block = 4;
     const unsigned grid = (unsigned)ceil_div64(c.T, waves_per_block);
     const int per = (int)ceil_div64(c.E, WAVE);
+    KernelBracket kb(MOE_KERNEL_TOPK, s);
 #define MOE_TOPK_CASE(P)                                                                          \
     topk_kernel<P><<<grid, waves_per_block * WAVE, 0, s>>>(logits, c.T, c.E, c.K, topk_idx, topk_w)
     if (per <= 1) MOE_TOPK_CASE(1);

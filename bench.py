@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--workload", default="qwen3_235b_T65536_bf16_zipf",
                     help="a name from workloads.CONFIGS, or sweep:<T> for the uniform-routing sweep point")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel (extra untimed steps)")
     return ap.parse_args()
 

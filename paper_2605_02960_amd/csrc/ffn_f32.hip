@@ -20,7 +20,7 @@ int32_t launch_ffn_f32(const moe_config_t& c, const float* x, const int32_t* per
     int32_t* table = static_cast<int32_t*>(ws);
     float* act = act_tap ? act_tap
                          : reinterpret_cast<float*>(static_cast<char*>(ws) + tile_table_bytes(c, F32_BM));
-    int32_t st = launch_build_tile_table(c, offsets, F32_BM, table, s);
+    int32_t st = launch_build_tile_table(c, offsets, F32_BM, table, nullptr, s);
     if (st != MOE_OK) return st;
     const unsigned tiles = (unsigned)max_row_tiles(c, F32_BM);
 

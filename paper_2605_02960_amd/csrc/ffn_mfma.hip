@@ -1,6 +1,6 @@
 // Grouped SwiGLU expert FFN on the gfx950 matrix cores (bf16 x bf16 -> f32 MFMA): the ragged
 // per-expert GEMMs of Sec. 4.2 of the paper, run with every expert of the layer resident
-// (Sec. 6.2).  Two launches over the device-built row-tile table:
+// (Sec. 6.2).  Two launches over the device-built tile tables:
 //   gate/up : act[p, i]  = SiLU(x_p . Wg_e[i,:]) * (x_p . Wu_e[i,:])   rounded once to bf16
 //   down    : y[p, h]    = act[p,:] . Wd_e[h,:]                          float32
 // Rows of x are gathered through perm while the token tile is loaded (no permuted copy of x).
@@ -9,13 +9,26 @@
 // 256 weight rows x 64 (K).  For gate/up the 256 weight rows are 128 rows of Wg and the same
 // 128 rows of Wu, so that a lane holds g and u of one output element side by side.  Each wave
 // owns 64 rows x 128 weight rows = 2 x 4 MFMA 32x32x16 blocks (128 accumulator registers).
-// The weight fragment is the MFMA "A" operand and the token fragment the "B" operand, so a lane
-// ends up with 4 consecutive output columns of one row and stores them as one vector.
+// The token fragment is the MFMA "A" operand and the weight fragment the "B" operand; the
+// wave's weight rows are interleaved over its output columns so that a lane ends up with 2
+// (gate/up) or 4 (down) adjacent output columns and 32 lanes store whole 128-byte lines.
 //
 // LDS.  A tile is [256 rows][64 bf16] = 128 bytes per row in 8 chunks of 16 bytes; chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which makes both the 16-byte stores of the loader
 // and the 16-byte fragment reads of the MFMA operands free of bank conflicts.  Two stages
 // (2 x 64 KB) are double-buffered with one barrier per K step.
+//
+// Pipeline.  Global loads are full 128-byte lines per row (one K step of one row), staged in two
+// register sets: the tile for K step k+2 is requested while step k is multiplied, so every request
+// has two K steps of MFMA work to hide behind.  The kernel is persistent (one workgroup per CU):
+// the loads that a tile's last two K steps would issue are the first two K steps of the
+// workgroup's NEXT tile, so consecutive tiles chain without draining the pipeline and the
+// epilogue's stores overlap the next tile's loads.
+//
+// Launch order.  Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b % 8).
+// Every XCD gets one contiguous range of the launch-order list (see tiles.hip), which walks an
+// expert's output in blocks of 8 x 4 tiles, so the 32 tiles in flight on an XCD share token rows
+// and weight rows in that XCD's L2.
 #include "common.h"
 
 namespace moe {
@@ -23,12 +36,13 @@ namespace moe {
 namespace {
 
 constexpr int BM = 256;        // rows per tile
-constexpr int BNW = 256;       // weight rows per tile
 constexpr int BK = 64;         // bf16 per K step
 constexpr int ROW_BYTES = BK * 2;
 constexpr int TILE_BYTES = 256 * ROW_BYTES;         // 32 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;         // tokens + weights
 constexpr int THREADS = 512;
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+constexpr int GROUP_ROWS = 8, GROUP_COLS = 4;       // tile block one XCD works on at a time
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
@@ -40,8 +54,9 @@ struct MfmaArgs {
     const char* B0;         // Wg (gate/up) or Wd (down): [E][N][Kd] bf16
     const char* B1;         // Wu (gate/up)
     int32_t N;              // output columns (I or H)
-    int32_t Kd;             // contraction length (H or I)
-    const int32_t* table;
+    int32_t Kd;             // contraction length (H or I), a multiple of 128
+    const int32_t* table;   // row tiles: [0] = count, then (expert, first row) pairs
+    const int32_t* order;   // launch slot -> rt << 8 | ct
     const int32_t* offsets;
     char* C;                // act [P,I] bf16 or y [P,H] f32
     int32_t nct;            // column tiles
@@ -51,52 +66,113 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
     return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u;
 }
 
+// One output tile as seen by one thread's loader and epilogue.
+struct TileCtx {
+    int row0, row_end, n0;
+    uint32_t a_off[4], b_off[4];   // byte offsets of the thread's 4 token rows / 4 weight rows
+    const char* b0e;               // expert's Wg / Wd
+    const char* b1e;               // expert's Wu
+};
+
+// Everything of a tile except the weight-row offsets (which are cheap to recompute and are only
+// filled in when the tile is about to be loaded, to keep registers free during the K loop).
+template <int MODE>
+__device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, int lr, int lc) {
+    constexpr int NCOLS = (MODE == MODE_GATE_UP) ? 128 : 256;
+    const int packed = a.order[L];
+    const int rt = packed >> 8, ct = packed & 255;
+    const int e = a.table[1 + 2 * rt];
+    t.row0 = a.table[2 + 2 * rt];
+    t.row_end = min(a.offsets[e + 1], t.row0 + BM);
+    t.n0 = ct * NCOLS;
+    const size_t wbytes = (size_t)a.N * a.Kd * 2;
+    t.b0e = a.B0 + (size_t)e * wbytes;
+    t.b1e = (MODE == MODE_GATE_UP) ? a.B1 + (size_t)e * wbytes : t.b0e;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int r = min(t.row0 + lr + 64 * i, t.row_end - 1);      // rows past the group's end re-read its last row
+        const uint32_t src = a.perm ? (uint32_t)(a.perm[r] / a.kdiv) : (uint32_t)r;
+        t.a_off[i] = src * a.lda_bytes + lc * 16;
+    }
+}
+// Weight row held by LDS row R of the weight tile.  A wave's 32-row MFMA blocks are interleaved
+// over the output columns (block nj, lane j <-> column NB*j + nj of the wave's column range, NB
+// blocks per range), so that after the MFMA one lane holds NB adjacent output columns of a row
+// and a store instruction writes whole 128-byte lines.
+template <int MODE>
+__device__ __forceinline__ int weight_col_of_lds_row(int R) {
+    if (MODE == MODE_GATE_UP) {          // rows 0..127 gate, 128..255 up; 64 columns per wave, NB = 2
+        const int h = R & 127;
+        return (h & 64) + 2 * (h & 31) + ((h >> 5) & 1);
+    }
+    return (R & 128) + 4 * (R & 31) + ((R >> 5) & 3);   // 128 columns per wave, NB = 4
+}
+template <int MODE>
+__device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int lr, int lc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int wr = t.n0 + weight_col_of_lds_row<MODE>(lr + 64 * i);
+        wr = min(wr, a.N - 1);
+        t.b_off[i] = (uint32_t)wr * (uint32_t)(a.Kd * 2) + lc * 16;
+    }
+}
+
+// Epilogue.  The token fragment is the MFMA "A" operand and the weight fragment the "B" operand:
+// acc[nj][mi][v] belongs to token row mi*32 + (v/4)*8 + fh*4 + v%4 of the wave's 64 rows and to
+// output column NB*fr + nj of the wave's column range.  Lanes 0..31 of one store instruction
+// therefore write one contiguous run of a row (128 bytes of bf16 act, 512 bytes of f32 y).
+template <int MODE>
+__device__ __forceinline__ void store_tile(f32x16 (&acc)[4][2], const MfmaArgs& a, const TileCtx& t,
+                                           int wm, int wn, int fr, int fh) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = t.row0 + wm * 64 + mi * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
+            if (m >= t.row_end) continue;
+            if (MODE == MODE_GATE_UP) {
+                const int n = t.n0 + wn * 64 + 2 * fr;
+                if (n >= a.N) continue;
+                const uint32_t lo = f32_to_bf16_bits(silu_mul(acc[0][mi][v], acc[2][mi][v]));
+                const uint32_t hi = f32_to_bf16_bits(silu_mul(acc[1][mi][v], acc[3][mi][v]));
+                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N + n) =
+                    lo | (hi << 16);
+            } else {
+                const int n = t.n0 + wn * 128 + 4 * fr;
+                if (n >= a.N) continue;
+                f32x4 o = {acc[0][mi][v], acc[1][mi][v], acc[2][mi][v], acc[3][mi][v]};
+                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n) = o;
+            }
+        }
+    }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr int NCOLS = (MODE == MODE_GATE_UP) ? 128 : 256;   // output columns per tile
-
-    // XCD-aware tile assignment: workgroups are dealt round-robin to the 8 XCDs, so workgroup b
-    // runs on XCD b % 8; give every XCD one contiguous range of tiles (column tile fastest), so
-    // that the tiles resident on one XCD at a time share token rows and weight panels in its L2.
-    const int n_rt = a.table[0];
-    const int total = n_rt * a.nct;
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return;
-    const int L = (blockIdx.x & 7) * per_xcd + slot;
-    if (L >= total) return;
-    const int rt = L / a.nct, ct = L - rt * a.nct;
-    const int e = a.table[1 + 2 * rt];
-    const int row0 = a.table[2 + 2 * rt];
-    const int row_end = min(a.offsets[e + 1], row0 + BM);
-    const int n0 = ct * NCOLS;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 3, wn = wave >> 2;
 
+    // ---- this workgroup's tiles: slots s, s + nslots, ... of its XCD's range of the launch order
+    const int total = a.table[0] * a.nct;
+    const int per_xcd = (total + 7) >> 3;
+    const int xcd = blockIdx.x & 7;
+    const int nslots = gridDim.x >> 3;
+    int slot = blockIdx.x >> 3;
+    const int l_end = min((xcd + 1) * per_xcd, total);
+    int L = xcd * per_xcd + slot;
+    if (slot >= per_xcd || L >= l_end) return;
+
     // ---- loader: thread handles chunk lc of rows lr + 64*i, i = 0..3, of both tiles
     const int lr = tid >> 3, lc = tid & 7;
     const uint32_t st_off = lr * ROW_BYTES + ((lc ^ ((lr >> 1) & 7)) << 4);
-    uint32_t a_off[4], b_off[4];
-    const char* b0e = a.B0 + (size_t)e * a.N * a.Kd * 2;
-    const char* b1e = (MODE == MODE_GATE_UP) ? a.B1 + (size_t)e * a.N * a.Kd * 2 : b0e;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int r = row0 + lr + 64 * i;
-        r = min(r, row_end - 1);
-        const uint32_t src = a.perm ? (uint32_t)(a.perm[r] / a.kdiv) : (uint32_t)r;
-        a_off[i] = src * a.lda_bytes + lc * 16;
-        int wr = (MODE == MODE_GATE_UP) ? n0 + lr + 64 * (i & 1) : n0 + lr + 64 * i;
-        wr = min(wr, a.N - 1);
-        b_off[i] = (uint32_t)wr * (uint32_t)(a.Kd * 2) + lc * 16;
-    }
 
     // ---- fragment read offsets
     const int fr = lane & 31, fh = lane >> 5;
     const int sw = (fr >> 1) & 7;
-    uint32_t frag_off[4];   // per kk: byte offset inside a row
+    uint32_t frag_off[4];   // per 16-wide K slice: byte offset inside a row
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) frag_off[kk] = (uint32_t)(((kk * 2 + fh) ^ sw) << 4);
     const uint32_t xa_row = (wm * 64 + fr) * ROW_BYTES;                    // + mi*32 rows
@@ -110,22 +186,15 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
 
     f32x16 acc[4][2];
-#pragma unroll
-    for (int nj = 0; nj < 4; ++nj)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nj][mi][v] = 0.f;
+    u32x4 ra0[4], rb0[4], ra1[4], rb1[4];   // the two register sets of staged global loads
 
-    // Two register sets of staged global loads: the tile for K step kt+2 is requested while step
-    // kt is being multiplied, so every request has two K steps of MFMA work to hide its latency.
-    u32x4 ra0[4], rb0[4], ra1[4], rb1[4];
-#define MOE_GLOAD(SET_, KT_)                                                              \
+#define MOE_GLOAD(SET_, CTX_, KT_)                                                        \
     {                                                                                     \
-        const uint32_t kb = (uint32_t)min((KT_), KT - 1) * ROW_BYTES;                     \
+        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                  \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                   \
-            ra##SET_[i] = *reinterpret_cast<const u32x4*>(a.A + (a_off[i] + kb));         \
-            rb##SET_[i] = *reinterpret_cast<const u32x4*>(((i < 2 || MODE == MODE_DOWN) ? b0e : b1e) + (b_off[i] + kb)); \
+            ra##SET_[i] = *reinterpret_cast<const u32x4*>(a.A + (CTX_.a_off[i] + kb));    \
+            rb##SET_[i] = *reinterpret_cast<const u32x4*>(                                \
+                ((i < 2 || MODE == MODE_DOWN) ? CTX_.b0e : CTX_.b1e) + (CTX_.b_off[i] + kb)); \
         }                                                                                 \
     }
 #define MOE_LSTORE(SET_, STAGE_)                                                          \
@@ -147,75 +216,84 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                 *reinterpret_cast<const bf16x8*>(st + wb_row[nj] + frag_off[kk]);         \
             _Pragma("unroll") for (int nj = 0; nj < 4; ++nj)                              \
                 _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) acc[nj][mi] =            \
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[nj], xa[mi], acc[nj][mi], 0, 0, 0); \
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[mi], wb[nj], acc[nj][mi], 0, 0, 0); \
         }                                                                                 \
     }
 
-    const int KT = a.Kd / BK;
-    MOE_GLOAD(0, 0);
-    MOE_GLOAD(1, 1);
+    const int KT = a.Kd / BK;   // even, >= 2
+    TileCtx cur, nxt;
+    load_ctx<MODE>(cur, a, L, lr, lc);
+    fill_b_off<MODE>(cur, a, lr, lc);
+    MOE_GLOAD(0, cur, 0);
+    MOE_GLOAD(1, cur, 1);
     MOE_LSTORE(0, 0);
     __syncthreads();
-    int kt = 0;
-    for (; kt + 1 < KT; kt += 2) {
-        MOE_GLOAD(0, kt + 2);
+
+    // Invariant at the top of every K-step pair (kt even): LDS stage 0 holds step kt, register
+    // set 1 holds (or is receiving) step kt+1, register set 0 is free.
+    for (;;) {
+        slot += nslots;
+        L += nslots;
+        const bool has_next = slot < per_xcd && L < l_end;
+        if (has_next) load_ctx<MODE>(nxt, a, L, lr, lc);
+        else nxt = cur;   // nothing follows: the two trailing loads re-read this tile (harmless)
+
+#pragma unroll
+        for (int nj = 0; nj < 4; ++nj)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[nj][mi][v] = 0.f;
+
+        for (int kt = 0; kt < KT - 2; kt += 2) {
+            MOE_GLOAD(0, cur, kt + 2);
+            MOE_COMPUTE(0);
+            MOE_LSTORE(1, 1);
+            __syncthreads();
+            MOE_GLOAD(1, cur, kt + 3);
+            MOE_COMPUTE(1);
+            MOE_LSTORE(0, 0);
+            __syncthreads();
+        }
+        // last pair of this tile: its two loads are steps 0 and 1 of the next tile
+        fill_b_off<MODE>(nxt, a, lr, lc);
+        MOE_GLOAD(0, nxt, 0);
         MOE_COMPUTE(0);
         MOE_LSTORE(1, 1);
         __syncthreads();
-        MOE_GLOAD(1, kt + 3);
+        MOE_GLOAD(1, nxt, 1);
         MOE_COMPUTE(1);
         MOE_LSTORE(0, 0);
         __syncthreads();
+
+        store_tile<MODE>(acc, a, cur, wm, wn, fr, fh);
+        if (!has_next) break;
+        cur = nxt;
     }
-    if (kt < KT) MOE_COMPUTE(0);
 #undef MOE_GLOAD
 #undef MOE_LSTORE
 #undef MOE_COMPUTE
+}
 
-    // ---- epilogue.  acc[nj][mi][v]: row = mi*32 + fr, column = (v/4)*8 + fh*4 + v%4 of the block
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-        const int m = row0 + wm * 64 + mi * 32 + fr;
-        if (m >= row_end) continue;
-        if (MODE == MODE_GATE_UP) {
-            uint16_t* crow = reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N;
-#pragma unroll
-            for (int nj = 0; nj < 2; ++nj)
-#pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    const int n = n0 + wn * 64 + nj * 32 + vg * 8 + fh * 4;
-                    if (n >= a.N) continue;
-                    uint16_t h[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        h[q] = f32_to_bf16_bits(silu_mul(acc[nj][mi][vg * 4 + q], acc[nj + 2][mi][vg * 4 + q]));
-                    uint2 o;
-                    o.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                    o.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-                    *reinterpret_cast<uint2*>(crow + n) = o;
-                }
-        } else {
-            float* crow = reinterpret_cast<float*>(a.C) + (size_t)m * a.N;
-#pragma unroll
-            for (int nj = 0; nj < 4; ++nj)
-#pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    const int n = n0 + wn * 128 + nj * 32 + vg * 8 + fh * 4;
-                    if (n >= a.N) continue;
-                    float4 o = make_float4(acc[nj][mi][vg * 4 + 0], acc[nj][mi][vg * 4 + 1],
-                                           acc[nj][mi][vg * 4 + 2], acc[nj][mi][vg * 4 + 3]);
-                    *reinterpret_cast<float4*>(crow + n) = o;
-                }
-        }
-    }
+struct FfnWs {
+    size_t table, first, order_gu, order_dn, act, total;
+};
+FfnWs ffn_ws_layout(const moe_config_t& c) {
+    const size_t P = (size_t)c.T * c.K;
+    FfnWs w{};
+    size_t o = 0;
+    w.table = o; o += tile_table_bytes(c, BM);
+    w.first = o; o += align_up(sizeof(int32_t) * (c.E + 1), 256);
+    w.order_gu = o; o += tile_order_bytes(c, BM, (int)ceil_div64(c.I, 128));
+    w.order_dn = o; o += tile_order_bytes(c, BM, (int)ceil_div64(c.H, 256));
+    w.act = o; o += align_up(P * c.I * 2, 256);
+    w.total = o;
+    return w;
 }
 
 }  // namespace
 
-size_t ffn_mfma_ws_bytes(const moe_config_t& c) {
-    const size_t P = (size_t)c.T * c.K;
-    return tile_table_bytes(c, BM) + align_up(P * c.I * 2, 256);
-}
+size_t ffn_mfma_ws_bytes(const moe_config_t& c) { return ffn_ws_layout(c).total; }
 
 int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* perm,
                         const int32_t* offsets, const void* wg, const void* wu, const void* wd,
@@ -226,27 +304,41 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     if (c.w_dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
     const int64_t P = (int64_t)c.T * c.K;
     if (P == 0) return MOE_OK;
-    // 32-bit byte offsets are used on the load side
+    // 32-bit byte offsets are used on the load side; column tiles are packed in 8 bits
     if ((uint64_t)c.T * c.H * 2 > 0xFFFFFFFFull || (uint64_t)P * c.I * 2 > 0xFFFFFFFFull ||
-        (uint64_t)c.I * c.H * 2 > 0xFFFFFFFFull)
+        (uint64_t)c.I * c.H * 2 > 0xFFFFFFFFull || c.I > 128 * 256 || c.H > 256 * 256)
         return MOE_ERR_UNSUPPORTED;
 
-    int32_t* table = static_cast<int32_t*>(ws);
-    char* act = act_tap ? static_cast<char*>(act_tap)
-                        : static_cast<char*>(ws) + tile_table_bytes(c, BM);
-    int32_t st = launch_build_tile_table(c, offsets, BM, table, s);
+    const FfnWs w = ffn_ws_layout(c);
+    char* ws8 = static_cast<char*>(ws);
+    int32_t* table = reinterpret_cast<int32_t*>(ws8 + w.table);
+    int32_t* first = reinterpret_cast<int32_t*>(ws8 + w.first);
+    int32_t* order_gu = reinterpret_cast<int32_t*>(ws8 + w.order_gu);
+    int32_t* order_dn = reinterpret_cast<int32_t*>(ws8 + w.order_dn);
+    char* act = act_tap ? static_cast<char*>(act_tap) : ws8 + w.act;
+    const int nct_gu = (int)ceil_div64(c.I, 128), nct_dn = (int)ceil_div64(c.H, 256);
+    int32_t st = launch_build_tile_table(c, offsets, BM, table, first, s);
+    if (st != MOE_OK) return st;
+    st = launch_build_tile_order(c, first, nct_gu, GROUP_ROWS, GROUP_COLS, order_gu, s);
+    if (st != MOE_OK) return st;
+    st = launch_build_tile_order(c, first, nct_dn, GROUP_ROWS, GROUP_COLS, order_dn, s);
     if (st != MOE_OK) return st;
 
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_GATE_UP>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_BYTES) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_DOWN>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_BYTES) != hipSuccess)
+    // one persistent workgroup per compute unit (the 128 KB of LDS allow no second one)
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return MOE_ERR_LAUNCH_FAILED;
-        attr_done = true;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_GATE_UP>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_DOWN>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return MOE_ERR_LAUNCH_FAILED;
+        n_cu = prop.multiProcessorCount;
     }
-    const int64_t mrt = max_row_tiles(c, BM);
+    const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
 
     MfmaArgs g{};
     g.A = static_cast<const char*>(x);
@@ -258,13 +350,13 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     g.N = c.I;
     g.Kd = c.H;
     g.table = table;
+    g.order = order_gu;
     g.offsets = offsets;
     g.C = act;
-    g.nct = (int32_t)ceil_div64(c.I, 128);
+    g.nct = nct_gu;
     {
-        const int64_t grid = ceil_div64(mrt * g.nct, 8) * 8;
         KernelBracket kb(MOE_KERNEL_GATE_UP, s);
-        ffn_mfma_kernel<MODE_GATE_UP><<<(unsigned)grid, THREADS, 2 * STAGE_BYTES, s>>>(g);
+        ffn_mfma_kernel<MODE_GATE_UP><<<grid, THREADS, LDS_BYTES, s>>>(g);
     }
     MfmaArgs d{};
     d.A = act;
@@ -276,13 +368,13 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.N = c.H;
     d.Kd = c.I;
     d.table = table;
+    d.order = order_dn;
     d.offsets = offsets;
     d.C = reinterpret_cast<char*>(y_perm);
-    d.nct = (int32_t)ceil_div64(c.H, 256);
+    d.nct = nct_dn;
     {
-        const int64_t grid = ceil_div64(mrt * d.nct, 8) * 8;
         KernelBracket kb(MOE_KERNEL_DOWN, s);
-        ffn_mfma_kernel<MODE_DOWN><<<(unsigned)grid, THREADS, 2 * STAGE_BYTES, s>>>(d);
+        ffn_mfma_kernel<MODE_DOWN><<<grid, THREADS, LDS_BYTES, s>>>(d);
     }
     return launch_status();
 }

@@ -7,7 +7,8 @@ namespace moe {
 
 __global__ __launch_bounds__(1024) void build_tile_table_kernel(const int32_t* __restrict__ offsets,
                                                                int E, int bm,
-                                                               int32_t* __restrict__ table) {
+                                                               int32_t* __restrict__ table,
+                                                               int32_t* __restrict__ first_out) {
     __shared__ int32_t first[1024 + 1];
     const int e = threadIdx.x;
     int32_t n = 0, o = 0;
@@ -28,6 +29,7 @@ __global__ __launch_bounds__(1024) void build_tile_table_kernel(const int32_t* _
         table[0] = acc;
     }
     __syncthreads();
+    if (first_out && e <= E) first_out[e] = first[e];
     if (e < E) {
         const int32_t t0 = first[e];
         for (int i = 0; i < n; ++i) {
@@ -38,8 +40,41 @@ __global__ __launch_bounds__(1024) void build_tile_table_kernel(const int32_t* _
 }
 
 int32_t launch_build_tile_table(const moe_config_t& c, const int32_t* offsets, int bm,
-                                int32_t* table, hipStream_t s) {
-    build_tile_table_kernel<<<1, 1024, 0, s>>>(offsets, c.E, bm, table);
+                                int32_t* table, int32_t* first_out, hipStream_t s) {
+    build_tile_table_kernel<<<1, 1024, 0, s>>>(offsets, c.E, bm, table, first_out);
+    return launch_status();
+}
+
+// Launch order of the output tiles (row tile rt, column tile ct), packed as rt << 8 | ct.
+// Inside one expert, row tiles are taken in groups of `gr` and column tiles in groups of `gc`;
+// a group of (up to) gr x gc tiles is listed row by row before the next column group starts.
+// Workgroups that run at the same time on one XCD therefore cover a compact block of the
+// expert's output and share its token rows and weight rows in that XCD's L2.  An expert with a
+// single row tile degenerates to column-fastest order (all its tiles share the token rows).
+__global__ __launch_bounds__(256) void build_tile_order_kernel(const int32_t* __restrict__ first,
+                                                              int nct, int gr, int gc,
+                                                              int32_t* __restrict__ order) {
+    const int e = blockIdx.x;
+    const int rt0 = first[e];
+    const int n = first[e + 1] - rt0;
+    const int total = n * nct;
+    int32_t* out = order + (size_t)rt0 * nct;
+    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+        const int g = i / (gr * nct);
+        const int rem = i - g * gr * nct;
+        const int gsz = min(gr, n - g * gr);
+        const int cg = rem / (gc * gsz);
+        const int rem2 = rem - cg * gc * gsz;
+        const int gw = min(gc, nct - cg * gc);
+        const int r = rem2 / gw;
+        const int c = rem2 - r * gw;
+        out[i] = ((rt0 + g * gr + r) << 8) | (cg * gc + c);
+    }
+}
+
+int32_t launch_build_tile_order(const moe_config_t& c, const int32_t* first, int nct, int gr, int gc,
+                                int32_t* order, hipStream_t s) {
+    build_tile_order_kernel<<<c.E, 256, 0, s>>>(first, nct, gr, gc, order);
     return launch_status();
 }
 

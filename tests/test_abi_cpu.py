@@ -48,7 +48,7 @@ def test_config_validation_and_workspace(L):
     assert all(s % 256 == 0 for s in sizes)
     bad = [
         (dict(K=0), -2), (dict(K=129), -2), (dict(K=33, E=64), -2), (dict(E=1025), -2), (dict(T=-1), -2),
-        (dict(H=4000), -2), (dict(I=1500), -2), (dict(x_dtype=2), -3), (dict(w_dtype=7), -3),
+        (dict(H=4032), -2), (dict(I=1472), -2), (dict(x_dtype=2), -3), (dict(w_dtype=7), -3),
         (dict(w_dtype=moe.DTYPE_F32), -3), (dict(out_dtype=2), -3), (dict(flags=1), -6),
         (dict(T=2 ** 28), -2),
     ]
@@ -66,7 +66,7 @@ def test_config_validation_and_workspace(L):
 
 def test_argument_errors_leave_before_any_launch(L):
     """Null and misaligned arguments are rejected on the host (no GPU needed to see that)."""
-    c = moe.make_config(64, 128, 8, 2, 64, moe.DTYPE_BF16, moe.DTYPE_BF16)
+    c = moe.make_config(64, 128, 8, 2, 128, moe.DTYPE_BF16, moe.DTYPE_BF16)
     p = ctypes.c_void_p
     fake = p(0x1000)        # never dereferenced: validation fails first
     assert L.moe_route(ctypes.byref(c), None, fake, None, fake, fake, fake, None, 0, None) == -1
@@ -82,7 +82,7 @@ def test_argument_errors_leave_before_any_launch(L):
     assert L.moe_combine(ctypes.byref(c), fake, fake, None, fake, None) == -1
     assert L.moe_prefill_layer(ctypes.byref(c), fake, fake, None, fake, fake, fake, None, None, None, fake, None,
                                fake, 1024, None) == -5
-    c8 = moe.make_config(64, 128, 8, 2, 64, moe.DTYPE_BF16, moe.DTYPE_FP8_E4M3)
+    c8 = moe.make_config(64, 128, 8, 2, 128, moe.DTYPE_BF16, moe.DTYPE_FP8_E4M3)
     assert L.moe_grouped_ffn(ctypes.byref(c8), fake, fake, fake, fake, fake, fake, None, None, None, None, None,
                              None, fake, fake, 1 << 30, None) == -1   # fp8 needs scales
     assert L.moe_quantize_rows_e4m3(fake, 4, 12, fake, fake, None) == -2

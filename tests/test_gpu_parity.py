@@ -175,7 +175,7 @@ def _bf16_checks(w, d, g, cfg, r, info, tokens):
 
 
 def test_bf16_small_skewed_with_empty_experts():
-    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name="bf16_small_zipf", T=700, H=256, E=32, K=4, I=192)
+    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name="bf16_small_zipf", T=700, H=256, E=32, K=4, I=384)
     d, g, cfg, r, info = _layer_case(w)
     assert int((r["counts"] == 0).sum()) >= 0
     _bf16_checks(w, d, g, cfg, r, info, None)

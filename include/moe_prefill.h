@@ -142,8 +142,10 @@ int32_t moe_quantize_rows_e4m3(const void *src_bf16, int64_t rows, int32_t cols,
  * ordered by ascending expert index; topk_w = softmax over the selected logits
  * (equal to the full softmax renormalised over the selection).
  *   x [T,H] (x_dtype), w_router [E,H] F32, bias [E] F32 or NULL,
- *   logits_out [T,E] F32 or NULL (then T*E floats of ws are used),
- *   topk_idx [T,K] int32, topk_w [T,K] F32. */
+ *   logits_out [T,E] F32 or NULL (then the logits live in ws),
+ *   topk_idx [T,K] int32, topk_w [T,K] F32.
+ *   ws: moe_workspace_bytes(cfg, MOE_CALL_ROUTE) bytes; it may be NULL only for F32 activations
+ *   with logits_out given (BF16 activations keep a bf16 split of w_router there). */
 int32_t moe_route(const moe_config_t *cfg, const void *x, const float *w_router, const float *bias,
                   float *logits_out, int32_t *topk_idx, float *topk_w, void *ws, size_t ws_bytes,
                   void *stream);

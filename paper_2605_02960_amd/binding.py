@@ -141,7 +141,7 @@ def moe_route(cfg, x, w_router, bias=None, want_logits=True, stream=None):
     idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device=dev)
     w = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device=dev)
     logits = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device=dev) if want_logits else None
-    ws, n = (None, 0) if want_logits else _ws(cfg, CALL_ROUTE, dev)
+    ws, n = _ws(cfg, CALL_ROUTE, dev)
     _check(lib().moe_route(ctypes.byref(cfg), _p(x), _p(w_router), _p(bias), _p(logits), _p(idx), _p(w),
                            _p(ws), n, _stream(stream)), "moe_route")
     return idx, w, logits

@@ -36,7 +36,12 @@ int32_t check_config(const moe_config_t* c) {
     return MOE_OK;
 }
 
-size_t route_ws(const moe_config_t& c) { return align_up((size_t)c.T * c.E * sizeof(float), 256); }
+// [logits T*E f32 (used only when the caller passes no logits buffer)][bf16 path: split router weight]
+size_t route_logits_ws(const moe_config_t& c) { return align_up((size_t)c.T * c.E * sizeof(float), 256); }
+bool route_uses_mfma(const moe_config_t& c) { return c.x_dtype == MOE_DTYPE_BF16; }
+size_t route_ws(const moe_config_t& c) {
+    return route_logits_ws(c) + (route_uses_mfma(c) ? router_mfma_ws_bytes(c) : 0);
+}
 size_t ffn_ws(const moe_config_t& c) {
     return c.w_dtype == MOE_DTYPE_F32 ? ffn_f32_ws_bytes(c) : ffn_mfma_ws_bytes(c);
 }
@@ -59,6 +64,7 @@ LayerWs layer_ws(const moe_config_t& c) {
     l.y = take(P * c.H * 4);
     size_t sub = permute_ws_bytes(c);
     if (ffn_ws(c) > sub) sub = ffn_ws(c);
+    if (route_ws(c) > sub) sub = route_ws(c);
     l.sub = take(sub);
     l.total = o;
     return l;
@@ -124,14 +130,20 @@ int32_t moe_route(const moe_config_t* cfg, const void* x, const float* w_router,
     if (!w_router || (!empty && (!x || !topk_idx || !topk_w))) return MOE_ERR_NULL_PTR;
     if (empty) return MOE_OK;
     float* logits = logits_out;
-    if (!logits) {
+    const bool mfma = route_uses_mfma(*cfg);
+    if (!logits || mfma) {
         if (!ws) return MOE_ERR_NULL_PTR;
         if (!aligned(ws, 256)) return MOE_ERR_UNALIGNED;
         if (ws_bytes < route_ws(*cfg)) return MOE_ERR_WORKSPACE_TOO_SMALL;
-        logits = static_cast<float*>(ws);
+        if (!logits) logits = static_cast<float*>(ws);
     }
+    if (mfma && !aligned(x, 16)) return MOE_ERR_UNALIGNED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = launch_router_logits(*cfg, x, w_router, bias, logits, s);
+    if (mfma)
+        st = launch_router_logits_mfma(*cfg, x, w_router, bias, logits,
+                                       static_cast<char*>(ws) + route_logits_ws(*cfg), s);
+    else
+        st = launch_router_logits(*cfg, x, w_router, bias, logits, s);
     if (st != MOE_OK) return st;
     return launch_topk(*cfg, logits, topk_idx, topk_w, s);
 }
@@ -218,7 +230,7 @@ int32_t moe_prefill_layer(const moe_config_t* cfg, const void* x, const float* w
     void* sub = w8 + l.sub;
     const size_t sub_bytes = l.total - l.sub;
 
-    st = moe_route(cfg, x, w_router, bias, logits, idx, tw, nullptr, 0, stream);
+    st = moe_route(cfg, x, w_router, bias, logits, idx, tw, sub, sub_bytes, stream);
     if (st != MOE_OK) return st;
     st = moe_permute(cfg, idx, nullptr, counts, offsets, perm, inv, nullptr, sub, sub_bytes, stream);
     if (st != MOE_OK) return st;

@@ -53,6 +53,10 @@ struct KernelBracket {
 // logits [T,E] f32 = x [T,H] (f32 or bf16 bits) . w_router[E,H]^T (+bias); then top-k.
 int32_t launch_router_logits(const moe_config_t& c, const void* x, const float* w_router,
                              const float* bias, float* logits, hipStream_t s);
+// ---- router_mfma.hip : bf16 activations, float32 router weight split into three bf16 parts
+size_t router_mfma_ws_bytes(const moe_config_t& c);
+int32_t launch_router_logits_mfma(const moe_config_t& c, const void* x, const float* w_router,
+                                  const float* bias, float* logits, void* ws, hipStream_t s);
 int32_t launch_topk(const moe_config_t& c, const float* logits, int32_t* topk_idx, float* topk_w,
                     hipStream_t s);
 

@@ -43,7 +43,7 @@ def test_config_validation_and_workspace(L):
     ok = moe.make_config(8192, 4096, 128, 8, 1536, moe.DTYPE_BF16, moe.DTYPE_BF16)
     sizes = [moe.moe_workspace_bytes(ok, c) for c in range(5)]
     assert sizes[moe.CALL_COMBINE] == 0
-    assert sizes[moe.CALL_ROUTE] == 8192 * 128 * 4
+    assert sizes[moe.CALL_ROUTE] == 8192 * 128 * 4 + 3 * 128 * 4096 * 2      # logits + bf16 split of the router weight
     assert sizes[moe.CALL_PREFILL_LAYER] > sizes[moe.CALL_GROUPED_FFN] >= 65536 * 1536 * 2
     assert all(s % 256 == 0 for s in sizes)
     bad = [

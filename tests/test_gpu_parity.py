@@ -185,6 +185,20 @@ def test_bf16_small_skewed_with_empty_experts():
     assert torch.equal(r2["out"], r["out"]) and torch.equal(r2["y_perm"], r["y_perm"])
 
 
+def test_bf16_router_ragged_expert_and_token_tiles():
+    """E = 160 (one full and one partial 128-expert tile), T = 300 (partial 128-token tiles), with a
+    router bias: the matrix-core router against the float64 logits, selection bit-exact."""
+    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name="bf16_router_ragged", T=300, H=384, E=160, K=6, I=128)
+    d, g, cfg, r, info = _layer_case(w)
+    l_ref = mo.router_logits(d["x"], d["w_router"], d["bias"])
+    assert gu.max_err_over_rms(r["logits"].cpu().numpy(), l_ref) <= 2e-6     # float32 accumulation of exact products
+    _bf16_checks(w, d, g, cfg, r, info, None)
+    # want_logits=False: logits live in the workspace, same routing
+    idx2, w2, _ = moe.moe_route(cfg, g["x"], g["w_router"], g["bias"], want_logits=False)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, r["topk_idx"]) and torch.equal(w2, r["topk_w"])
+
+
 def test_bf16_group_sizes_around_tile_edges():
     """Groups of 0, 1, 255, 256, 257 and 600 rows (K=1, routing forced by the router bias)."""
     sizes = [0, 1, 255, 256, 257, 600, 0, 3]

@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel (extra untimed steps)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -102,10 +104,19 @@ def main():
         moe.moe_prefill_layer(cfg, g["x"], g["w_router"], g["bias"], g["w_gate"], g["w_up"], g["w_down"],
                               out=out, ws=ws, stream=stream)
 
+    cal_src = cal_dst = None
+    if a.copy_calibration:
+        cal_src = torch.full((1 << 28,), 1.5, dtype=torch.float32, device=dev)     # 1 GiB
+        cal_dst = torch.empty_like(cal_src)
+
     ev = HipEvents()
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
+    if a.copy_calibration:
+        # the warm-up steps above have pushed cal_src out of every cache: 1 GiB read, 1 GiB written
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` steps; the dominant kernel is bracketed by HIP events
     pairs = [(ev.create(), ev.create()) for _ in range(a.steps)]

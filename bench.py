@@ -79,9 +79,6 @@ def main():
         moe_build.build()
     w = workloads.sweep_point(int(a.workload.split(":")[1])) if a.workload.startswith("sweep:") \
         else workloads.CONFIGS[a.workload]
-    if w.dtype == "fp8":
-        print("bench.py: the fp8 workload is not wired into the bench yet", file=sys.stderr)
-        sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     d = workloads.generate(w)
@@ -95,13 +92,23 @@ def main():
 
     g = {k: up(v) for k, v in d.items()}
     dt = moe.DTYPE_F32 if w.dtype == "fp32" else moe.DTYPE_BF16
-    cfg = moe.make_config(w.T, w.H, w.E, w.K, w.I, dt, dt, moe.DTYPE_F32)
+    wdt = moe.DTYPE_FP8_E4M3 if w.dtype == "fp8" else dt
+    cfg = moe.make_config(w.T, w.H, w.E, w.K, w.I, dt, wdt, moe.DTYPE_F32)
+    scales = {}
+    if w.dtype == "fp8":
+        # expert weights are stored as e4m3 with per-output-channel scales: quantised once, outside the timed region
+        for name, rows, cols in (("w_gate", w.E * w.I, w.H), ("w_up", w.E * w.I, w.H), ("w_down", w.E * w.H, w.I)):
+            q, sc = moe.moe_quantize_rows_e4m3(g[name].reshape(rows, cols))
+            torch.cuda.synchronize()
+            g[name] = q
+            scales["s_" + name[2:]] = sc
     ws = torch.empty(moe.moe_workspace_bytes(cfg, moe.CALL_PREFILL_LAYER), dtype=torch.uint8, device=dev)
     out = torch.empty((w.T, w.H), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
     def step():
         moe.moe_prefill_layer(cfg, g["x"], g["w_router"], g["bias"], g["w_gate"], g["w_up"], g["w_down"],
+                              scales.get("s_gate"), scales.get("s_up"), scales.get("s_down"),
                               out=out, ws=ws, stream=stream)
 
     cal_src = cal_dst = None
@@ -153,7 +160,7 @@ def main():
                    "routing": "zipf-biased" if w.zipf_bias else "uniform", "routed_rows": rows},
         "tokens_per_s": round(w.T / (ms_per_step * 1e-3), 1),
         "pct_of_mfma_peak": round(100.0 * value / peak, 2),
-        "roofline": {"kernel": "grouped gate/up GEMM + SwiGLU (ffn_mfma_kernel<gate_up>)", "bound": "mfma",
+        "roofline": {"kernel": "grouped gate/up GEMM + SwiGLU (ffn_mfma_kernel<gate_up>), %s MFMA" % w.dtype, "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4), "traffic": traffic,
                      "ms_per_launch": round(gate_up_ms, 4)},
@@ -180,7 +187,8 @@ def main():
         n = min(a.cpu_sample_tokens, w.T)
         tok = np.sort(np.random.default_rng(0).choice(w.T, size=n, replace=False))
         c0 = time.perf_counter()
-        mo.moe_layer(d["x"], d["w_router"], d["w_gate"], d["w_up"], d["w_down"], w.K, d["bias"], tokens=tok)
+        mo.moe_layer(d["x"], d["w_router"], d["w_gate"], d["w_up"], d["w_down"], w.K, d["bias"], tokens=tok,
+                     fp8=(w.dtype == "fp8"))
         c1 = time.perf_counter()
         # counted work of what the oracle evaluated: router for all T tokens, experts for the sample
         fl = 2.0 * w.H * w.E * w.T + 6.0 * w.H * w.I * n * w.K

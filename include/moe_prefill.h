@@ -76,7 +76,8 @@ typedef enum moe_call {
  *   w_dtype   F32 (needs x F32), BF16 (needs x BF16) or FP8_E4M3 (needs x BF16;
  *             weights are e4m3 codes with one float scale per output channel)
  *   out_dtype F32 or BF16 (the bf16 result is the float32 result rounded once)
- *   BF16/FP8 paths need H % 128 == 0 and I % 128 == 0; the F32 path takes any size.
+ *   The BF16 path needs H % 128 == 0 and I % 128 == 0, the FP8 path H % 256 == 0 and
+ *   I % 256 == 0; the F32 path takes any size.
  */
 typedef struct moe_config {
     int32_t T, H, E, K, I;

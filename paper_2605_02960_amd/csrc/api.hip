@@ -25,9 +25,12 @@ int32_t check_config(const moe_config_t* c) {
             if (c->x_dtype != MOE_DTYPE_F32) return MOE_ERR_BAD_DTYPE;
             break;
         case MOE_DTYPE_BF16:
-        case MOE_DTYPE_FP8_E4M3:
             if (c->x_dtype != MOE_DTYPE_BF16) return MOE_ERR_BAD_DTYPE;
             if (c->H % 128 != 0 || c->I % 128 != 0) return MOE_ERR_BAD_SHAPE;
+            break;
+        case MOE_DTYPE_FP8_E4M3:
+            if (c->x_dtype != MOE_DTYPE_BF16) return MOE_ERR_BAD_DTYPE;
+            if (c->H % 256 != 0 || c->I % 256 != 0) return MOE_ERR_BAD_SHAPE;
             break;
         default:
             return MOE_ERR_BAD_DTYPE;

@@ -41,8 +41,12 @@ constexpr int ROW_BYTES = BK * 2;
 constexpr int TILE_BYTES = 256 * ROW_BYTES;         // 32 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;         // tokens + weights
 constexpr int THREADS = 512;
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-constexpr int GROUP_ROWS = 8, GROUP_COLS = 4;       // tile block one XCD works on at a time
+constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * 256 * 4;   // + two buffers of 256 row scales (fp8)
+#ifndef MOE_GROUP_ROWS
+#define MOE_GROUP_ROWS 8
+#define MOE_GROUP_COLS 4
+#endif
+constexpr int GROUP_ROWS = MOE_GROUP_ROWS, GROUP_COLS = MOE_GROUP_COLS;   // tile block one XCD works on at a time
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
@@ -54,7 +58,11 @@ struct MfmaArgs {
     const char* B0;         // Wg (gate/up) or Wd (down): [E][N][Kd] bf16
     const char* B1;         // Wu (gate/up)
     int32_t N;              // output columns (I or H)
-    int32_t Kd;             // contraction length (H or I), a multiple of 128
+    uint32_t ldb_bytes;     // bytes of one weight row (contraction length x element size)
+    int32_t KT;             // K steps of 128 bytes per row (64 bf16 or 128 fp8), even
+    const float* sA;        // fp8: scale of sorted row p (of its x row for gate/up, of its act row for down)
+    const float* sB0;       // fp8: per-output-channel scales [E][N] of B0
+    const float* sB1;       // fp8: same for B1
     const int32_t* table;   // row tiles: [0] = count, then (expert, first row) pairs
     const int32_t* order;   // launch slot -> rt << 8 | ct
     const int32_t* offsets;
@@ -72,6 +80,7 @@ struct TileCtx {
     uint32_t a_off[4], b_off[4];   // byte offsets of the thread's 4 token rows / 4 weight rows
     const char* b0e;               // expert's Wg / Wd
     const char* b1e;               // expert's Wu
+    int e;
 };
 
 // Everything of a tile except the weight-row offsets (which are cheap to recompute and are only
@@ -82,10 +91,11 @@ __device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, i
     const int packed = a.order[L];
     const int rt = packed >> 8, ct = packed & 255;
     const int e = a.table[1 + 2 * rt];
+    t.e = e;
     t.row0 = a.table[2 + 2 * rt];
     t.row_end = min(a.offsets[e + 1], t.row0 + BM);
     t.n0 = ct * NCOLS;
-    const size_t wbytes = (size_t)a.N * a.Kd * 2;
+    const size_t wbytes = (size_t)a.N * a.ldb_bytes;
     t.b0e = a.B0 + (size_t)e * wbytes;
     t.b1e = (MODE == MODE_GATE_UP) ? a.B1 + (size_t)e * wbytes : t.b0e;
 #pragma unroll
@@ -113,7 +123,7 @@ __device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int lr
     for (int i = 0; i < 4; ++i) {
         int wr = t.n0 + weight_col_of_lds_row<MODE>(lr + 64 * i);
         wr = min(wr, a.N - 1);
-        t.b_off[i] = (uint32_t)wr * (uint32_t)(a.Kd * 2) + lc * 16;
+        t.b_off[i] = (uint32_t)wr * a.ldb_bytes + lc * 16;
     }
 }
 
@@ -121,33 +131,58 @@ __device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int lr
 // acc[nj][mi][v] belongs to token row mi*32 + (v/4)*8 + fh*4 + v%4 of the wave's 64 rows and to
 // output column NB*fr + nj of the wave's column range.  Lanes 0..31 of one store instruction
 // therefore write one contiguous run of a row (128 bytes of bf16 act, 512 bytes of f32 y).
-template <int MODE>
+// fp8: the accumulators hold sums of code products; the float scales of the row and of the output
+// channel are applied here, in float32: value = acc * (s_row * s_channel).
+template <int MODE, bool FP8>
 __device__ __forceinline__ void store_tile(f32x16 (&acc)[4][2], const MfmaArgs& a, const TileCtx& t,
-                                           int wm, int wn, int fr, int fh) {
+                                           int wm, int wn, int fr, int fh, const float* row_scale) {
+    const int n = (MODE == MODE_GATE_UP) ? t.n0 + wn * 64 + 2 * fr : t.n0 + wn * 128 + 4 * fr;
+    if (n >= a.N) return;
+    float sc0[4] = {1.f, 1.f, 1.f, 1.f};   // per-channel scales of acc[0..3]
+    if (FP8) {
+        const size_t sb = (size_t)t.e * a.N + n;
+        if (MODE == MODE_GATE_UP) {
+            sc0[0] = a.sB0[sb]; sc0[1] = a.sB0[sb + 1];
+            sc0[2] = a.sB1[sb]; sc0[3] = a.sB1[sb + 1];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sc0[q] = a.sB0[sb + q];
+        }
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int m = t.row0 + wm * 64 + mi * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
+            const int lrow = wm * 64 + mi * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);   // row inside the tile
+            const int m = t.row0 + lrow;
             if (m >= t.row_end) continue;
+            float r[4] = {acc[0][mi][v], acc[1][mi][v], acc[2][mi][v], acc[3][mi][v]};
+            if (FP8) {
+                const float sr = row_scale[lrow];   // staged in LDS at the start of the tile
+#pragma unroll
+                for (int q = 0; q < 4; ++q) r[q] *= sr * sc0[q];
+            }
             if (MODE == MODE_GATE_UP) {
-                const int n = t.n0 + wn * 64 + 2 * fr;
-                if (n >= a.N) continue;
-                const uint32_t lo = f32_to_bf16_bits(silu_mul(acc[0][mi][v], acc[2][mi][v]));
-                const uint32_t hi = f32_to_bf16_bits(silu_mul(acc[1][mi][v], acc[3][mi][v]));
+                const uint32_t lo = f32_to_bf16_bits(silu_mul(r[0], r[2]));
+                const uint32_t hi = f32_to_bf16_bits(silu_mul(r[1], r[3]));
                 *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N + n) =
                     lo | (hi << 16);
             } else {
-                const int n = t.n0 + wn * 128 + 4 * fr;
-                if (n >= a.N) continue;
-                f32x4 o = {acc[0][mi][v], acc[1][mi][v], acc[2][mi][v], acc[3][mi][v]};
+                f32x4 o = {r[0], r[1], r[2], r[3]};
                 *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n) = o;
             }
         }
     }
 }
 
-template <int MODE>
+// 32 bytes of one LDS row (two swizzled 16-byte chunks) as one fp8 MFMA operand
+__device__ __forceinline__ i32x8 load_frag8(const char* row, uint32_t off0, uint32_t off1) {
+    const u32x4 lo = *reinterpret_cast<const u32x4*>(row + off0);
+    const u32x4 hi = *reinterpret_cast<const u32x4*>(row + off1);
+    return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+}
+
+template <int MODE, bool FP8>
 __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -172,9 +207,15 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // ---- fragment read offsets
     const int fr = lane & 31, fh = lane >> 5;
     const int sw = (fr >> 1) & 7;
-    uint32_t frag_off[4];   // per 16-wide K slice: byte offset inside a row
+    // bf16: MFMA k16 slice kk takes chunk kk*2 + fh of the row (16 bytes per lane);
+    // fp8 : MFMA k64 slice kk takes chunks kk*4 + fh*2 and the next one (32 bytes per lane);
+    // in both cases lane half fh and slice kk read chunk index kk*2 + fh in units of their own size.
+    uint32_t frag_off[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = (uint32_t)(((kk * 2 + fh) ^ sw) << 4);
+    for (int c = 0; c < 4; ++c) {
+        if (FP8) frag_off[c] = (uint32_t)((((c >> 1) * 4 + fh * 2 + (c & 1)) ^ sw) << 4);   // c = kk*2 + half
+        else frag_off[c] = (uint32_t)(((c * 2 + fh) ^ sw) << 4);                             // c = kk
+    }
     const uint32_t xa_row = (wm * 64 + fr) * ROW_BYTES;                    // + mi*32 rows
     uint32_t wb_row[4];
 #pragma unroll
@@ -205,22 +246,38 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             *reinterpret_cast<u32x4*>(base + TILE_BYTES + i * 64 * ROW_BYTES) = rb##SET_[i]; \
         }                                                                                 \
     }
+#define MOE_LOAD_FRAG8(PTR_, KK_) load_frag8((PTR_), frag_off[(KK_) * 2], frag_off[(KK_) * 2 + 1])
 #define MOE_COMPUTE(STAGE_)                                                               \
     {                                                                                     \
         const char* st = smem + (STAGE_) * STAGE_BYTES;                                   \
-        _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                \
-            bf16x8 xa[2], wb[4];                                                          \
-            _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) xa[mi] =                     \
-                *reinterpret_cast<const bf16x8*>(st + xa_row + mi * 32 * ROW_BYTES + frag_off[kk]); \
-            _Pragma("unroll") for (int nj = 0; nj < 4; ++nj) wb[nj] =                     \
-                *reinterpret_cast<const bf16x8*>(st + wb_row[nj] + frag_off[kk]);         \
-            _Pragma("unroll") for (int nj = 0; nj < 4; ++nj)                              \
-                _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) acc[nj][mi] =            \
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[mi], wb[nj], acc[nj][mi], 0, 0, 0); \
+        if constexpr (!FP8) {                                                             \
+            _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                            \
+                bf16x8 xa[2], wb[4];                                                      \
+                _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) xa[mi] =                 \
+                    *reinterpret_cast<const bf16x8*>(st + xa_row + mi * 32 * ROW_BYTES + frag_off[kk]); \
+                _Pragma("unroll") for (int nj = 0; nj < 4; ++nj) wb[nj] =                 \
+                    *reinterpret_cast<const bf16x8*>(st + wb_row[nj] + frag_off[kk]);     \
+                _Pragma("unroll") for (int nj = 0; nj < 4; ++nj)                          \
+                    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) acc[nj][mi] =        \
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[mi], wb[nj], acc[nj][mi], 0, 0, 0); \
+            }                                                                             \
+        } else {                                                                          \
+            _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                            \
+                i32x8 xa[2];                                                              \
+                _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                          \
+                    xa[mi] = MOE_LOAD_FRAG8(st + xa_row + mi * 32 * ROW_BYTES, kk);       \
+                /* zero scale operands select the unscaled v_mfma_f32_32x32x64_f8f6f4 */   \
+                _Pragma("unroll") for (int nj = 0; nj < 4; ++nj) {                        \
+                    const i32x8 wb = MOE_LOAD_FRAG8(st + wb_row[nj], kk);                 \
+                    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) acc[nj][mi] =        \
+                        __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                  \
+                            xa[mi], wb, acc[nj][mi], 0, 0, 0, 0, 0, 0);                   \
+                }                                                                         \
+            }                                                                             \
         }                                                                                 \
     }
 
-    const int KT = a.Kd / BK;   // even, >= 2
+    const int KT = a.KT;   // even, >= 2
     TileCtx cur, nxt;
     load_ctx<MODE>(cur, a, L, lr, lc);
     fill_b_off<MODE>(cur, a, lr, lc);
@@ -229,6 +286,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     MOE_LSTORE(0, 0);
     __syncthreads();
 
+    int tile_parity = 0;
     // Invariant at the top of every K-step pair (kt even): LDS stage 0 holds step kt, register
     // set 1 holds (or is receiving) step kt+1, register set 0 is free.
     for (;;) {
@@ -237,6 +295,9 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         const bool has_next = slot < per_xcd && L < l_end;
         if (has_next) load_ctx<MODE>(nxt, a, L, lr, lc);
         else nxt = cur;   // nothing follows: the two trailing loads re-read this tile (harmless)
+        float* row_scale = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES) + (tile_parity << 8);
+        if (FP8 && tid < BM) row_scale[tid] = a.sA[min(cur.row0 + tid, cur.row_end - 1)];
+        tile_parity ^= 1;   // the buffer is read in this tile's epilogue, many barriers from here
 
 #pragma unroll
         for (int nj = 0; nj < 4; ++nj)
@@ -266,29 +327,57 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         MOE_LSTORE(0, 0);
         __syncthreads();
 
-        store_tile<MODE>(acc, a, cur, wm, wn, fr, fh);
+        store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fh, row_scale);
         if (!has_next) break;
         cur = nxt;
     }
 #undef MOE_GLOAD
 #undef MOE_LSTORE
 #undef MOE_COMPUTE
+#undef MOE_LOAD_FRAG8
 }
 
 struct FfnWs {
-    size_t table, first, order_gu, order_dn, act, total;
+    size_t table, first, order_gu, order_dn, act, xq, sx, sxp, act_q, sa, total;
 };
 FfnWs ffn_ws_layout(const moe_config_t& c) {
     const size_t P = (size_t)c.T * c.K;
+    const bool fp8 = c.w_dtype == MOE_DTYPE_FP8_E4M3;
     FfnWs w{};
     size_t o = 0;
-    w.table = o; o += tile_table_bytes(c, BM);
-    w.first = o; o += align_up(sizeof(int32_t) * (c.E + 1), 256);
-    w.order_gu = o; o += tile_order_bytes(c, BM, (int)ceil_div64(c.I, 128));
-    w.order_dn = o; o += tile_order_bytes(c, BM, (int)ceil_div64(c.H, 256));
-    w.act = o; o += align_up(P * c.I * 2, 256);
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes ? bytes : 1, 256); return at; };
+    w.table = take(tile_table_bytes(c, BM));
+    w.first = take(sizeof(int32_t) * (c.E + 1));
+    w.order_gu = take(tile_order_bytes(c, BM, (int)ceil_div64(c.I, 128)));
+    w.order_dn = take(tile_order_bytes(c, BM, (int)ceil_div64(c.H, 256)));
+    w.act = take(P * c.I * 2);
+    if (fp8) {
+        w.xq = take((size_t)c.T * c.H);
+        w.sx = take((size_t)c.T * 4);
+        w.sxp = take(P * 4);
+        w.act_q = take(P * c.I);
+        w.sa = take(P * 4);
+    }
     w.total = o;
     return w;
+}
+
+// sxp[p] = sx[perm[p] / K]: the scale of the x row behind sorted row p
+__global__ __launch_bounds__(256) void gather_row_scales_kernel(const float* __restrict__ sx,
+                                                               const int32_t* __restrict__ perm,
+                                                               int K, int P, float* __restrict__ sxp) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < P) sxp[p] = sx[perm[p] / K];
+}
+
+template <bool FP8>
+int32_t set_kernel_attributes() {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_GATE_UP, FP8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_DOWN, FP8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+        return MOE_ERR_LAUNCH_FAILED;
+    return MOE_OK;
 }
 
 }  // namespace
@@ -300,13 +389,17 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
                         const float* s_gate, const float* s_up, const float* s_down, void* act_tap,
                         uint8_t* act_q_tap, float* act_scale_tap, float* y_perm, void* ws,
                         hipStream_t s) {
-    (void)s_gate; (void)s_up; (void)s_down; (void)act_q_tap; (void)act_scale_tap;
-    if (c.w_dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
+    const bool fp8 = c.w_dtype == MOE_DTYPE_FP8_E4M3;
+    if (!fp8 && c.w_dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
     const int64_t P = (int64_t)c.T * c.K;
     if (P == 0) return MOE_OK;
-    // 32-bit byte offsets are used on the load side; column tiles are packed in 8 bits
-    if ((uint64_t)c.T * c.H * 2 > 0xFFFFFFFFull || (uint64_t)P * c.I * 2 > 0xFFFFFFFFull ||
-        (uint64_t)c.I * c.H * 2 > 0xFFFFFFFFull || c.I > 128 * 256 || c.H > 256 * 256)
+    const int esz = fp8 ? 1 : 2;                // bytes per operand element
+    const int kstep = 128 / esz;                // elements per 128-byte K step
+    // the K loop runs in pairs of 128-byte steps; 32-bit byte offsets are used on the load side;
+    // column tiles are packed in 8 bits
+    if (c.H % (2 * kstep) != 0 || c.I % (2 * kstep) != 0) return MOE_ERR_BAD_SHAPE;
+    if ((uint64_t)c.T * c.H * esz > 0xFFFFFFFFull || (uint64_t)P * c.I * esz > 0xFFFFFFFFull ||
+        (uint64_t)c.I * c.H * esz > 0xFFFFFFFFull || c.I > 128 * 256 || c.H > 256 * 256)
         return MOE_ERR_UNSUPPORTED;
 
     const FfnWs w = ffn_ws_layout(c);
@@ -331,24 +424,41 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return MOE_ERR_LAUNCH_FAILED;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_GATE_UP>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_DOWN>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+        if (set_kernel_attributes<false>() != MOE_OK || set_kernel_attributes<true>() != MOE_OK)
             return MOE_ERR_LAUNCH_FAILED;
         n_cu = prop.multiProcessorCount;
     }
     const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
 
+    // fp8: quantise the x rows once per token, and carry each sorted row's scale along
+    const char* a_gu = static_cast<const char*>(x);
+    uint8_t* act_q = nullptr;
+    float *sxp = nullptr, *sa = nullptr;
+    if (fp8) {
+        uint8_t* xq = reinterpret_cast<uint8_t*>(ws8 + w.xq);
+        float* sx = reinterpret_cast<float*>(ws8 + w.sx);
+        sxp = reinterpret_cast<float*>(ws8 + w.sxp);
+        act_q = act_q_tap ? act_q_tap : reinterpret_cast<uint8_t*>(ws8 + w.act_q);
+        sa = act_scale_tap ? act_scale_tap : reinterpret_cast<float*>(ws8 + w.sa);
+        st = launch_quantize_rows(x, c.T, c.H, xq, sx, s);
+        if (st != MOE_OK) return st;
+        gather_row_scales_kernel<<<(unsigned)ceil_div64(P, 256), 256, 0, s>>>(sx, perm, c.K, (int)P, sxp);
+        a_gu = reinterpret_cast<const char*>(xq);
+    }
+
     MfmaArgs g{};
-    g.A = static_cast<const char*>(x);
-    g.lda_bytes = (uint32_t)c.H * 2;
+    g.A = a_gu;
+    g.lda_bytes = (uint32_t)c.H * esz;
     g.perm = perm;
     g.kdiv = c.K;
     g.B0 = static_cast<const char*>(wg);
     g.B1 = static_cast<const char*>(wu);
     g.N = c.I;
-    g.Kd = c.H;
+    g.ldb_bytes = (uint32_t)c.H * esz;
+    g.KT = c.H / kstep;
+    g.sA = sxp;
+    g.sB0 = s_gate;
+    g.sB1 = s_up;
     g.table = table;
     g.order = order_gu;
     g.offsets = offsets;
@@ -356,17 +466,28 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     g.nct = nct_gu;
     {
         KernelBracket kb(MOE_KERNEL_GATE_UP, s);
-        ffn_mfma_kernel<MODE_GATE_UP><<<grid, THREADS, LDS_BYTES, s>>>(g);
+        if (fp8) ffn_mfma_kernel<MODE_GATE_UP, true><<<grid, THREADS, LDS_BYTES, s>>>(g);
+        else ffn_mfma_kernel<MODE_GATE_UP, false><<<grid, THREADS, LDS_BYTES, s>>>(g);
+    }
+    const char* a_dn = act;
+    if (fp8) {   // per-row e4m3 of the bf16 activations
+        st = launch_quantize_rows(act, P, c.I, act_q, sa, s);
+        if (st != MOE_OK) return st;
+        a_dn = reinterpret_cast<const char*>(act_q);
     }
     MfmaArgs d{};
-    d.A = act;
-    d.lda_bytes = (uint32_t)c.I * 2;
+    d.A = a_dn;
+    d.lda_bytes = (uint32_t)c.I * esz;
     d.perm = nullptr;
     d.kdiv = 1;
     d.B0 = static_cast<const char*>(wd);
     d.B1 = nullptr;
     d.N = c.H;
-    d.Kd = c.I;
+    d.ldb_bytes = (uint32_t)c.I * esz;
+    d.KT = c.I / kstep;
+    d.sA = sa;
+    d.sB0 = s_down;
+    d.sB1 = nullptr;
     d.table = table;
     d.order = order_dn;
     d.offsets = offsets;
@@ -374,7 +495,8 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.nct = nct_dn;
     {
         KernelBracket kb(MOE_KERNEL_DOWN, s);
-        ffn_mfma_kernel<MODE_DOWN><<<grid, THREADS, LDS_BYTES, s>>>(d);
+        if (fp8) ffn_mfma_kernel<MODE_DOWN, true><<<grid, THREADS, LDS_BYTES, s>>>(d);
+        else ffn_mfma_kernel<MODE_DOWN, false><<<grid, THREADS, LDS_BYTES, s>>>(d);
     }
     return launch_status();
 }

@@ -82,7 +82,7 @@ def test_argument_errors_leave_before_any_launch(L):
     assert L.moe_combine(ctypes.byref(c), fake, fake, None, fake, None) == -1
     assert L.moe_prefill_layer(ctypes.byref(c), fake, fake, None, fake, fake, fake, None, None, None, fake, None,
                                fake, 1024, None) == -5
-    c8 = moe.make_config(64, 128, 8, 2, 128, moe.DTYPE_BF16, moe.DTYPE_FP8_E4M3)
+    c8 = moe.make_config(64, 256, 8, 2, 256, moe.DTYPE_BF16, moe.DTYPE_FP8_E4M3)
     assert L.moe_grouped_ffn(ctypes.byref(c8), fake, fake, fake, fake, fake, fake, None, None, None, None, None,
                              None, fake, fake, 1 << 30, None) == -1   # fp8 needs scales
     assert L.moe_quantize_rows_e4m3(fake, 4, 12, fake, fake, None) == -2

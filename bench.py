@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel (extra untimed steps)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="saturation sweep: one JSON line per token count T of workloads.SWEEP_T (uniform routing)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -77,6 +79,8 @@ def main():
 
     if not os.path.exists(moe.lib_path()):
         moe_build.build()
+    if a.sweep:
+        return sweep(a, np, torch, moe, workloads)
     w = workloads.sweep_point(int(a.workload.split(":")[1])) if a.workload.startswith("sweep:") \
         else workloads.CONFIGS[a.workload]
     dev = "cuda:0"
@@ -200,6 +204,62 @@ def main():
             "tokens_per_s_experts_only": round(n / (c1 - c0), 2),
         }
     print(json.dumps(res))
+
+
+def sweep(a, np, torch, moe, workloads):
+    """GEMM-saturation sweep (the block-level analogue of the paper's MFU-versus-batch curve, Sec. 4.2
+    Fig. 3): grouped-FFN TFLOP/s against rows per expert, uniform routing, bf16, weights fixed."""
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def up(v):
+        if v is None:
+            return None
+        if v.dtype == np.uint16:
+            return torch.from_numpy(v.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(v).to(dev)
+
+    w0 = workloads.sweep_point(workloads.SWEEP_T[0])
+    g = {k: up(v) for k, v in workloads.generate(w0).items()}
+    ev = HipEvents()
+    for T in workloads.SWEEP_T:
+        w = workloads.sweep_point(T)
+        x = up(workloads.generate_x(w))
+        cfg = moe.make_config(w.T, w.H, w.E, w.K, w.I, moe.DTYPE_BF16, moe.DTYPE_BF16, moe.DTYPE_F32)
+        ws = torch.empty(moe.moe_workspace_bytes(cfg, moe.CALL_PREFILL_LAYER), dtype=torch.uint8, device=dev)
+        out = torch.empty((w.T, w.H), dtype=torch.float32, device=dev)
+        stream = torch.cuda.current_stream()
+
+        def step():
+            moe.moe_prefill_layer(cfg, x, g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], out=out, ws=ws,
+                                  stream=stream)
+
+        for _ in range(a.warmup):
+            step()
+        torch.cuda.synchronize()
+        gu, dn = [], []
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            p1, p2 = (ev.create(), ev.create()), (ev.create(), ev.create())
+            moe.moe_set_profile_events(moe.KERNEL_GATE_UP, *p1)
+            moe.moe_set_profile_events(moe.KERNEL_DOWN, *p2)
+            step()
+            gu.append(p1)
+            dn.append(p2)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / a.steps
+        moe.moe_set_profile_events(moe.KERNEL_GATE_UP, None, None)
+        moe.moe_set_profile_events(moe.KERNEL_DOWN, None, None)
+        gu_ms = float(np.mean([ev.elapsed_ms(*p) for p in gu]))
+        dn_ms = float(np.mean([ev.elapsed_ms(*p) for p in dn]))
+        rows = w.T * w.K
+        ffn = 6.0 * w.H * w.I * rows
+        print(json.dumps({"sweep": True, "T": T, "rows_per_expert": rows // w.E,
+                          "ffn_tflops": round(ffn / ((gu_ms + dn_ms) * 1e-3) / 1e12, 1),
+                          "gate_up_ms": round(gu_ms, 4), "down_ms": round(dn_ms, 4),
+                          "layer_ms": round(ms, 4),
+                          "layer_tflops": round((ffn + 2.0 * w.H * w.E * w.T) / (ms * 1e-3) / 1e12, 1)}), flush=True)
+        del x, ws, out
 
 
 if __name__ == "__main__":

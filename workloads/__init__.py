@@ -78,6 +78,23 @@ def zipf_bias(E):
     return (1.5 * np.log(1.0 / (e + 1.0))).astype(np.float32)
 
 
+def generate_x(w, seed=0, threads=None):
+    """Only the activations x [T,H] of `generate` (same values)."""
+    st = "fp32" if w.dtype == "fp32" else "bf16"
+    base = [BASE_SEED, w.cfg_id, seed]
+    threads = threads or min(16, os.cpu_count() or 1)
+    x = np.empty((w.T, w.H), dtype=np.float32 if st == "fp32" else np.uint16)
+    chunk = 2048
+
+    def fill_x(c):
+        n = min(chunk, w.T - c)
+        x[c:c + n] = _normal(base + [0, c], (n, w.H), 1.0, st)
+
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(fill_x, range(0, w.T, chunk)))
+    return x
+
+
 def generate(w, seed=0, threads=None):
     """All tensors of one layer.  Keys: x [T,H]; w_router [E,H] float32; bias [E]
     float32 or None; w_gate, w_up [E,I,H]; w_down [E,H,I].  x and the expert
@@ -89,23 +106,16 @@ def generate(w, seed=0, threads=None):
     sto = np.float32 if st == "fp32" else np.uint16
     out["w_router"] = _normal(base + [1], (w.E, w.H), 0.02, "fp32")
     out["bias"] = zipf_bias(w.E) if w.zipf_bias else None
-    x = np.empty((w.T, w.H), dtype=sto)
+    x = generate_x(w, seed, threads)
     wg = np.empty((w.E, w.I, w.H), dtype=sto)
     wu = np.empty((w.E, w.I, w.H), dtype=sto)
     wd = np.empty((w.E, w.H, w.I), dtype=sto)
-    chunk = 2048
-
-    def fill_x(c):
-        n = min(chunk, w.T - c)
-        x[c:c + n] = _normal(base + [0, c], (n, w.H), 1.0, st)
-
     def fill_e(e):
         wg[e] = _normal(base + [2, e], (w.I, w.H), 0.02, st)
         wu[e] = _normal(base + [3, e], (w.I, w.H), 0.02, st)
         wd[e] = _normal(base + [4, e], (w.H, w.I), 0.02, st)
 
     with ThreadPoolExecutor(threads) as ex:
-        list(ex.map(fill_x, range(0, w.T, chunk)))
         list(ex.map(fill_e, range(w.E)))
     out.update(x=x, w_gate=wg, w_up=wu, w_down=wd)
     return out

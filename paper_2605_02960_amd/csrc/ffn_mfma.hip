@@ -29,6 +29,8 @@
 // Every XCD gets one contiguous range of the launch-order list (see tiles.hip), which walks an
 // expert's output in blocks of 8 x 4 tiles, so the 32 tiles in flight on an XCD share token rows
 // and weight rows in that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -105,74 +107,119 @@ __device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, i
         t.a_off[i] = src * a.lda_bytes + lc * 16;
     }
 }
-// Weight row held by LDS row R of the weight tile.  A wave's 32-row MFMA blocks are interleaved
-// over the output columns (block nj, lane j <-> column NB*j + nj of the wave's column range, NB
-// blocks per range), so that after the MFMA one lane holds NB adjacent output columns of a row
-// and a store instruction writes whole 128-byte lines.
-template <int MODE>
+// MFMA block edge: bf16 uses v_mfma_f32_16x16x32_bf16 (less accumulator traffic per flop than
+// 32x32x16, measured ~5-8 % faster in this pipeline), fp8 uses v_mfma_f32_32x32x64_f8f6f4.
+#ifndef MOE_BF16_BLK
+#define MOE_BF16_BLK 32
+#endif
+template <bool FP8>
+struct Blk {
+    static constexpr int E = FP8 ? 32 : MOE_BF16_BLK;   // rows / columns of one MFMA block
+    static constexpr int NM = 64 / E;            // blocks along the wave's 64 token rows
+    static constexpr int NN = 128 / E;           // blocks along the wave's 128 weight rows
+    static constexpr int VLEN = E * E / 64;      // accumulator registers of one block
+    static constexpr int NBG = 64 / E;           // gate/up: adjacent output columns per lane
+};
+
+// Weight row held by LDS row R of the weight tile.  A wave's MFMA blocks are interleaved over
+// its output columns (block nj, lane j <-> column NB*j + nj of a column range, NB blocks per
+// range), so that after the MFMA one lane holds NB adjacent output columns of a row and a store
+// instruction writes whole 128-byte lines.
+template <int MODE, int BE>
 __device__ __forceinline__ int weight_col_of_lds_row(int R) {
-    if (MODE == MODE_GATE_UP) {          // rows 0..127 gate, 128..255 up; 64 columns per wave, NB = 2
-        const int h = R & 127;
-        return (h & 64) + 2 * (h & 31) + ((h >> 5) & 1);
+    if (MODE == MODE_GATE_UP) {          // rows 0..127 gate, 128..255 up; 64 columns per wave
+        const int w = R & 63;
+        return (R & 64) + (64 / BE) * (w % BE) + w / BE;
     }
-    return (R & 128) + 4 * (R & 31) + ((R >> 5) & 3);   // 128 columns per wave, NB = 4
+    const int w = R & 127;               // 128 columns per wave, in ranges of 4 blocks
+    const int nj = w / BE;
+    return (R & 128) + (nj >> 2) * (4 * BE) + 4 * (w % BE) + (nj & 3);
 }
-template <int MODE>
+template <int MODE, int BE>
 __device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int lr, int lc) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int wr = t.n0 + weight_col_of_lds_row<MODE>(lr + 64 * i);
+        int wr = t.n0 + weight_col_of_lds_row<MODE, BE>(lr + 64 * i);
         wr = min(wr, a.N - 1);
         t.b_off[i] = (uint32_t)wr * a.ldb_bytes + lc * 16;
     }
 }
 
 // Epilogue.  The token fragment is the MFMA "A" operand and the weight fragment the "B" operand:
-// acc[nj][mi][v] belongs to token row mi*32 + (v/4)*8 + fh*4 + v%4 of the wave's 64 rows and to
-// output column NB*fr + nj of the wave's column range.  Lanes 0..31 of one store instruction
-// therefore write one contiguous run of a row (128 bytes of bf16 act, 512 bytes of f32 y).
+// acc[nj][mi][v] belongs to token row mi*BE + (v/4)*8 + fq*4 + v%4 of the wave's 64 rows (fq =
+// lane / BE) and to the output column that weight_col_of_lds_row gives block nj, lane fr.  The BE
+// lanes with equal fq write one contiguous run of a row (128 bytes of bf16 act, 256 or 512 bytes
+// of f32 y) per store instruction.
 // fp8: the accumulators hold sums of code products; the float scales of the row and of the output
 // channel are applied here, in float32: value = acc * (s_row * s_channel).
-template <int MODE, bool FP8>
-__device__ __forceinline__ void store_tile(f32x16 (&acc)[4][2], const MfmaArgs& a, const TileCtx& t,
-                                           int wm, int wn, int fr, int fh, const float* row_scale) {
-    const int n = (MODE == MODE_GATE_UP) ? t.n0 + wn * 64 + 2 * fr : t.n0 + wn * 128 + 4 * fr;
-    if (n >= a.N) return;
-    float sc0[4] = {1.f, 1.f, 1.f, 1.f};   // per-channel scales of acc[0..3]
-    if (FP8) {
-        const size_t sb = (size_t)t.e * a.N + n;
-        if (MODE == MODE_GATE_UP) {
-            sc0[0] = a.sB0[sb]; sc0[1] = a.sB0[sb + 1];
-            sc0[2] = a.sB1[sb]; sc0[3] = a.sB1[sb + 1];
-        } else {
+template <int MODE, bool FP8, typename ACC>
+__device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+                                           const TileCtx& t, int wm, int wn, int fr, int fq,
+                                           const float* row_scale) {
+    constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN, VLEN = Blk<FP8>::VLEN;
+    constexpr int NBG = Blk<FP8>::NBG;
+    constexpr int NGRP = (MODE == MODE_GATE_UP) ? 1 : NN / 4;     // column ranges per wave
+    constexpr int NPER = (MODE == MODE_GATE_UP) ? NBG : 4;        // adjacent columns per lane and range
 #pragma unroll
-            for (int q = 0; q < 4; ++q) sc0[q] = a.sB0[sb + q];
+    for (int grp = 0; grp < NGRP; ++grp) {
+        const int n = (MODE == MODE_GATE_UP) ? t.n0 + wn * 64 + NBG * fr
+                                             : t.n0 + wn * 128 + grp * (4 * BE) + 4 * fr;
+        if (n >= a.N) continue;
+        float sg[NPER], su[NPER];   // per-channel scales (fp8): gate or down, and up
+#pragma unroll
+        for (int q = 0; q < NPER; ++q) {
+            sg[q] = FP8 ? a.sB0[(size_t)t.e * a.N + n + q] : 1.f;
+            su[q] = (FP8 && MODE == MODE_GATE_UP) ? a.sB1[(size_t)t.e * a.N + n + q] : 1.f;
+        }
+#pragma unroll
+        for (int mi = 0; mi < NM; ++mi) {
+#pragma unroll
+            for (int v = 0; v < VLEN; ++v) {
+                const int lrow = wm * 64 + mi * BE + (v >> 2) * 8 + fq * 4 + (v & 3);   // row inside the tile
+                const int m = t.row0 + lrow;
+                if (m >= t.row_end) continue;
+                const float sr = FP8 ? row_scale[lrow] : 1.f;   // staged in LDS at the start of the tile
+                if (MODE == MODE_GATE_UP) {
+                    uint16_t h[NPER];
+#pragma unroll
+                    for (int q = 0; q < NPER; ++q) {
+                        float g = acc[q][mi][v], u = acc[NBG + q][mi][v];
+                        if (FP8) {
+                            g *= sr * sg[q];
+                            u *= sr * su[q];
+                        }
+                        h[q] = f32_to_bf16_bits(silu_mul(g, u));
+                    }
+                    uint16_t* dst = reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N + n;
+                    if (NPER == 2) {
+                        *reinterpret_cast<uint32_t*>(dst) = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                    } else {
+                        uint2 o;
+                        o.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                        o.y = (uint32_t)h[NPER - 2] | ((uint32_t)h[NPER - 1] << 16);
+                        *reinterpret_cast<uint2*>(dst) = o;
+                    }
+                } else {
+                    float r[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        r[q] = acc[grp * 4 + q][mi][v];
+                        if (FP8) r[q] *= sr * sg[q];
+                    }
+                    f32x4 o = {r[0], r[1], r[2], r[3]};
+                    // y_perm is read back (by the combine) only after 8 GiB more have gone by: streaming store
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n));
+                }
+            }
         }
     }
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int lrow = wm * 64 + mi * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);   // row inside the tile
-            const int m = t.row0 + lrow;
-            if (m >= t.row_end) continue;
-            float r[4] = {acc[0][mi][v], acc[1][mi][v], acc[2][mi][v], acc[3][mi][v]};
-            if (FP8) {
-                const float sr = row_scale[lrow];   // staged in LDS at the start of the tile
-#pragma unroll
-                for (int q = 0; q < 4; ++q) r[q] *= sr * sc0[q];
-            }
-            if (MODE == MODE_GATE_UP) {
-                const uint32_t lo = f32_to_bf16_bits(silu_mul(r[0], r[2]));
-                const uint32_t hi = f32_to_bf16_bits(silu_mul(r[1], r[3]));
-                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N + n) =
-                    lo | (hi << 16);
-            } else {
-                f32x4 o = {r[0], r[1], r[2], r[3]};
-                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n) = o;
-            }
-        }
-    }
+}
+
+__device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
 // 32 bytes of one LDS row (two swizzled 16-byte chunks) as one fp8 MFMA operand
@@ -204,29 +251,30 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     const int lr = tid >> 3, lc = tid & 7;
     const uint32_t st_off = lr * ROW_BYTES + ((lc ^ ((lr >> 1) & 7)) << 4);
 
-    // ---- fragment read offsets
-    const int fr = lane & 31, fh = lane >> 5;
+    // ---- fragment read offsets.  Lane = (fq, fr): fr = row of the MFMA block, fq = which 16-byte
+    // (bf16) or 32-byte (fp8) piece of the block's K slice the lane supplies.
+    constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN;
+    constexpr int NG = 64 / BE;                 // lane groups = pieces per K slice
+    const int fr = lane % BE, fq = lane / BE;
     const int sw = (fr >> 1) & 7;
-    // bf16: MFMA k16 slice kk takes chunk kk*2 + fh of the row (16 bytes per lane);
-    // fp8 : MFMA k64 slice kk takes chunks kk*4 + fh*2 and the next one (32 bytes per lane);
-    // in both cases lane half fh and slice kk read chunk index kk*2 + fh in units of their own size.
+    // bf16: slice kk (8/NG per K step) takes chunk kk*NG + fq;
+    // fp8 : slice kk (2 per K step) takes chunks kk*4 + fq*2 and the next one.
     uint32_t frag_off[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        if (FP8) frag_off[c] = (uint32_t)((((c >> 1) * 4 + fh * 2 + (c & 1)) ^ sw) << 4);   // c = kk*2 + half
-        else frag_off[c] = (uint32_t)(((c * 2 + fh) ^ sw) << 4);                             // c = kk
+        if (FP8) frag_off[c] = (uint32_t)((((c >> 1) * 4 + fq * 2 + (c & 1)) ^ sw) << 4);   // c = kk*2 + half
+        else frag_off[c] = (uint32_t)((((c % (8 / NG)) * NG + fq) ^ sw) << 4);               // c = kk
     }
-    const uint32_t xa_row = (wm * 64 + fr) * ROW_BYTES;                    // + mi*32 rows
-    uint32_t wb_row[4];
-#pragma unroll
-    for (int nj = 0; nj < 4; ++nj) {
-        int r;
-        if (MODE == MODE_GATE_UP) r = (nj >> 1) * 128 + wn * 64 + (nj & 1) * 32 + fr;
-        else r = wn * 128 + nj * 32 + fr;
-        wb_row[nj] = TILE_BYTES + r * ROW_BYTES;
-    }
+    const uint32_t xa_row = (wm * 64 + fr) * ROW_BYTES;                    // + mi*BE rows
+    const uint32_t wb_base = TILE_BYTES + ((MODE == MODE_GATE_UP ? wn * 64 : wn * 128) + fr) * ROW_BYTES;
+    // block nj of the wave: gate/up: blocks 0..NN/2-1 are gate rows, the rest the matching up rows
+    auto wb_off = [](int nj) -> uint32_t {
+        if (MODE == MODE_GATE_UP) return (uint32_t)(((nj / (NN / 2)) * 128 + (nj % (NN / 2)) * BE) * ROW_BYTES);
+        return (uint32_t)(nj * BE * ROW_BYTES);
+    };
 
-    f32x16 acc[4][2];
+    typedef typename std::conditional<BE == 32, f32x16, f32x4>::type acc_t;
+    acc_t acc[NN][NM];
     u32x4 ra0[4], rb0[4], ra1[4], rb1[4];   // the two register sets of staged global loads
 
 #define MOE_GLOAD(SET_, CTX_, KT_)                                                        \
@@ -251,25 +299,26 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     {                                                                                     \
         const char* st = smem + (STAGE_) * STAGE_BYTES;                                   \
         if constexpr (!FP8) {                                                             \
-            _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                            \
-                bf16x8 xa[2], wb[4];                                                      \
-                _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) xa[mi] =                 \
-                    *reinterpret_cast<const bf16x8*>(st + xa_row + mi * 32 * ROW_BYTES + frag_off[kk]); \
-                _Pragma("unroll") for (int nj = 0; nj < 4; ++nj) wb[nj] =                 \
-                    *reinterpret_cast<const bf16x8*>(st + wb_row[nj] + frag_off[kk]);     \
-                _Pragma("unroll") for (int nj = 0; nj < 4; ++nj)                          \
-                    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) acc[nj][mi] =        \
-                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[mi], wb[nj], acc[nj][mi], 0, 0, 0); \
+            _Pragma("unroll") for (int kk = 0; kk < 8 / NG; ++kk) {                       \
+                bf16x8 xa[NM];                                                            \
+                _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) xa[mi] =                \
+                    *reinterpret_cast<const bf16x8*>(st + xa_row + mi * BE * ROW_BYTES + frag_off[kk]); \
+                _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) {                       \
+                    const bf16x8 wb =                                                     \
+                        *reinterpret_cast<const bf16x8*>(st + wb_base + wb_off(nj) + frag_off[kk]); \
+                    _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) acc[nj][mi] =       \
+                        mfma_bf16(xa[mi], wb, acc[nj][mi]);                               \
+                }                                                                         \
             }                                                                             \
         } else {                                                                          \
             _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                            \
-                i32x8 xa[2];                                                              \
-                _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                          \
-                    xa[mi] = MOE_LOAD_FRAG8(st + xa_row + mi * 32 * ROW_BYTES, kk);       \
+                i32x8 xa[NM];                                                             \
+                _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                         \
+                    xa[mi] = MOE_LOAD_FRAG8(st + xa_row + mi * BE * ROW_BYTES, kk);       \
                 /* zero scale operands select the unscaled v_mfma_f32_32x32x64_f8f6f4 */   \
-                _Pragma("unroll") for (int nj = 0; nj < 4; ++nj) {                        \
-                    const i32x8 wb = MOE_LOAD_FRAG8(st + wb_row[nj], kk);                 \
-                    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) acc[nj][mi] =        \
+                _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) {                       \
+                    const i32x8 wb = MOE_LOAD_FRAG8(st + wb_base + wb_off(nj), kk);       \
+                    _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) acc[nj][mi] =       \
                         __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                  \
                             xa[mi], wb, acc[nj][mi], 0, 0, 0, 0, 0, 0);                   \
                 }                                                                         \
@@ -280,7 +329,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     const int KT = a.KT;   // even, >= 2
     TileCtx cur, nxt;
     load_ctx<MODE>(cur, a, L, lr, lc);
-    fill_b_off<MODE>(cur, a, lr, lc);
+    fill_b_off<MODE, BE>(cur, a, lr, lc);
     MOE_GLOAD(0, cur, 0);
     MOE_GLOAD(1, cur, 1);
     MOE_LSTORE(0, 0);
@@ -300,11 +349,11 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         tile_parity ^= 1;   // the buffer is read in this tile's epilogue, many barriers from here
 
 #pragma unroll
-        for (int nj = 0; nj < 4; ++nj)
+        for (int nj = 0; nj < NN; ++nj)
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < NM; ++mi)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[nj][mi][v] = 0.f;
+                for (int v = 0; v < Blk<FP8>::VLEN; ++v) acc[nj][mi][v] = 0.f;
 
         for (int kt = 0; kt < KT - 2; kt += 2) {
             MOE_GLOAD(0, cur, kt + 2);
@@ -317,7 +366,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             __syncthreads();
         }
         // last pair of this tile: its two loads are steps 0 and 1 of the next tile
-        fill_b_off<MODE>(nxt, a, lr, lc);
+        fill_b_off<MODE, BE>(nxt, a, lr, lc);
         MOE_GLOAD(0, nxt, 0);
         MOE_COMPUTE(0);
         MOE_LSTORE(1, 1);
@@ -327,7 +376,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         MOE_LSTORE(0, 0);
         __syncthreads();
 
-        store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fh, row_scale);
+        store_tile<MODE, FP8, acc_t>(acc, a, cur, wm, wn, fr, fq, row_scale);
         if (!has_next) break;
         cur = nxt;
     }

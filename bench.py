@@ -9,7 +9,6 @@ own stream inside the timed region; `cpu_baseline` is the fp64 CPU oracle timed 
 token sample of the same workload.
 """
 import argparse
-import ctypes
 import json
 import os
 import sys
@@ -34,34 +33,15 @@ def parse():
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel (extra untimed steps)")
     ap.add_argument("--sweep", action="store_true",
                     help="saturation sweep: one JSON line per token count T of workloads.SWEEP_T (uniform routing)")
+    ap.add_argument("--stream", choices=["bf16", "fp8"], default=None,
+                    help="one-GPU weight streaming: expert weights of --layers layers come from pinned host memory "
+                         "through --slots device slots; one JSON line per token count with t_c, t_e and the thresholds")
+    ap.add_argument("--layers", type=int, default=6)
+    ap.add_argument("--slots", type=int, default=2)
+    ap.add_argument("--stream-tokens", type=str, default=None, help="comma-separated token counts for --stream")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
     return ap.parse_args()
-
-
-class HipEvents:
-    """Raw hipEvent_t pairs through the HIP runtime that torch already loaded."""
-
-    def __init__(self):
-        self.hip = ctypes.CDLL("libamdhip64.so")
-        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
-        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
-        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
-        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
-
-    def create(self):
-        e = ctypes.c_void_p()
-        assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
-        return e.value
-
-    def elapsed_ms(self, a, b):
-        assert self.hip.hipEventSynchronize(b) == 0
-        ms = ctypes.c_float()
-        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
-        return ms.value
-
-    def destroy(self, e):
-        self.hip.hipEventDestroy(e)
 
 
 def main():
@@ -81,6 +61,8 @@ def main():
         moe_build.build()
     if a.sweep:
         return sweep(a, np, torch, moe, workloads)
+    if a.stream:
+        return stream_mode(a, np, torch, moe, workloads)
     w = workloads.sweep_point(int(a.workload.split(":")[1])) if a.workload.startswith("sweep:") \
         else workloads.CONFIGS[a.workload]
     dev = "cuda:0"
@@ -120,7 +102,7 @@ def main():
         cal_src = torch.full((1 << 28,), 1.5, dtype=torch.float32, device=dev)     # 1 GiB
         cal_dst = torch.empty_like(cal_src)
 
-    ev = HipEvents()
+    ev = moe.HipEvents()
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
@@ -221,7 +203,7 @@ def sweep(a, np, torch, moe, workloads):
 
     w0 = workloads.sweep_point(workloads.SWEEP_T[0])
     g = {k: up(v) for k, v in workloads.generate(w0).items()}
-    ev = HipEvents()
+    ev = moe.HipEvents()
     for T in workloads.SWEEP_T:
         w = workloads.sweep_point(T)
         x = up(workloads.generate_x(w))
@@ -260,6 +242,114 @@ def sweep(a, np, torch, moe, workloads):
                           "layer_ms": round(ms, 4),
                           "layer_tflops": round((ffn + 2.0 * w.H * w.E * w.T) / (ms * 1e-3) / 1e12, 1)}), flush=True)
         del x, ws, out
+
+
+def stream_mode(a, np, torch, moe, workloads):
+    """One-GPU weight streaming (App. B.1 of the paper) against the saturation threshold (Eq. 1,
+    App. B.4 Eq. 3): layer 0 is resident (pure compute, t_c), later layers wait for their H2D
+    transfer at entry (t_e = their largest wall time)."""
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    fp8 = a.stream == "fp8"
+    base = workloads.QWEN3_32K_FP8 if fp8 else workloads.QWEN3_8K
+    tokens = [int(t) for t in a.stream_tokens.split(",")] if a.stream_tokens else \
+        ([32768, 131072, 262144] if fp8 else [16384, 65536, 131072])
+
+    def up(v):
+        if v is None:
+            return None
+        if v.dtype == np.uint16:
+            return torch.from_numpy(v.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(v).to(dev)
+
+    # two distinct layers of weights in pinned host memory, used alternately (bounds the pinned footprint)
+    host_layers = []
+    parts = ["w_gate", "w_up", "w_down"] + (["s_gate", "s_up", "s_down"] if fp8 else [])
+    g0 = None
+    for seed in range(2):
+        g = {k: up(v) for k, v in workloads.generate(base, seed=seed).items() if k != "x"}
+        if fp8:
+            for name, rows, cols in (("w_gate", base.E * base.I, base.H), ("w_up", base.E * base.I, base.H),
+                                     ("w_down", base.E * base.H, base.I)):
+                q, sc = moe.moe_quantize_rows_e4m3(g[name].reshape(rows, cols))
+                torch.cuda.synchronize()
+                g[name], g["s_" + name[2:]] = q, sc
+        h = {}
+        for pn in parts:
+            t = torch.empty(g[pn].shape, dtype=g[pn].dtype, pin_memory=True)
+            t.copy_(g[pn])
+            h[pn] = t
+        h["w_router"] = g["w_router"]
+        host_layers.append(h)
+        if g0 is None:
+            g0 = g
+        else:
+            del g
+    torch.cuda.synchronize()
+    ev = moe.HipEvents()
+    copy_stream = torch.cuda.Stream()
+    dt_w = moe.DTYPE_FP8_E4M3 if fp8 else moe.DTYPE_BF16
+    for T in tokens:
+        w = workloads.scaled(base, T=T)
+        cfg = moe.make_config(w.T, w.H, w.E, w.K, w.I, moe.DTYPE_BF16, dt_w, moe.DTYPE_F32)
+        x = up(workloads.generate_x(w))
+        ws = torch.empty(moe.moe_workspace_bytes(cfg, moe.CALL_PREFILL_LAYER), dtype=torch.uint8, device=dev)
+        out = torch.empty((w.T, w.H), dtype=torch.float32, device=dev)
+        nbytes = moe.moe_layer_weight_bytes(cfg)
+        slots = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(a.slots)]
+        # layer 0 resident in slot 0, in the call's slot layout
+        off = 0
+        for pn in parts:
+            nb = g0[pn].numel() * g0[pn].element_size()
+            slots[0][off:off + nb] = g0[pn].reshape(-1).view(torch.uint8)
+            off += (nb + 255) // 256 * 256
+        layers = [dict(host_layers[i % 2], bias=None, out=out) for i in range(a.layers)]
+        # transfer time of one layer on its own
+        torch.cuda.synchronize()
+        t_copy = []
+        for _ in range(2):
+            s0 = torch.cuda.Event(enable_timing=True)
+            s1 = torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(copy_stream):
+                s0.record()
+                off = 0
+                for pn in parts:
+                    nb = host_layers[1][pn].numel() * host_layers[1][pn].element_size()
+                    slots[-1][off:off + nb].copy_(host_layers[1][pn].reshape(-1).view(torch.uint8), non_blocking=True)
+                    off += (nb + 255) // 256 * 256
+                s1.record()
+            torch.cuda.synchronize()
+            t_copy.append(s0.elapsed_time(s1) * 1e-3)
+        t_ep = min(t_copy)
+        best = None
+        for rep in range(2):
+            torch.cuda.synchronize()
+            h0 = time.perf_counter()
+            pairs = moe.moe_prefill_layers_streamed(cfg, layers, x, slots, n_resident=1, ws=ws,
+                                                    copy_stream=copy_stream, events=ev, time_layers=True)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - h0
+            walls = [ev.elapsed_ms(*p) * 1e-3 for p in pairs]
+            if best is None or wall < best[0]:
+                best = (wall, walls)
+        wall, walls = best
+        t_c, t_e = walls[0], max(walls[1:])
+        f_tok = moe.moe_layer_flops_per_token(cfg)
+        c_dummy = f_tok * T
+        f_ach = c_dummy / t_c
+        t_eq1 = moe.moe_saturation_threshold_flops(t_ep, f_ach, 1.2)
+        t_eq3 = moe.moe_calibrated_threshold_flops(t_c, t_e, c_dummy, 1.2)
+        print(json.dumps({
+            "stream": a.stream, "T": T, "layers": a.layers, "slots": a.slots,
+            "layer_weight_GB": round(nbytes / 1e9, 3), "t_ep_ms": round(t_ep * 1e3, 2),
+            "h2d_GBps": round(nbytes / t_ep / 1e9, 1),
+            "t_c_ms": round(t_c * 1e3, 3), "t_e_ms": round(t_e * 1e3, 3),
+            "transfer_hidden": bool(t_e <= 1.05 * t_c),
+            "total_ms": round(wall * 1e3, 2), "tflops_layer0": round(f_ach / 1e12, 1),
+            "threshold_eq1_TFLOP": round(t_eq1 / 1e12, 1), "threshold_eq1_tokens": int(t_eq1 / f_tok),
+            "threshold_eq3_TFLOP": round(t_eq3 / 1e12, 1), "threshold_eq3_tokens": int(t_eq3 / f_tok),
+            "batch_TFLOP": round(c_dummy / 1e12, 1)}), flush=True)
+        del x, ws, out, slots
 
 
 if __name__ == "__main__":

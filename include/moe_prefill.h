@@ -195,6 +195,51 @@ int32_t moe_prefill_layer(const moe_config_t *cfg, const void *x, const float *w
                           const float *s_down, void *out, const moe_taps_t *taps, void *ws,
                           size_t ws_bytes, void *stream);
 
+/* ---- One-GPU weight streaming (the "one-GPU H2D streaming" mode of the weight streaming engine,
+ * App. B.1; offloading pipeline of Sec. 6.3) and the saturation threshold (Eq. 1; App. B.4 Eq. 3).
+ *
+ * The expert weights of all layers stay in PINNED HOST memory; the GPU holds n_slots layer
+ * slots of moe_layer_weight_bytes(cfg) bytes each.  Layer i runs from slot i % n_slots.  The copy
+ * stream transfers a layer into its slot as soon as the layer that used the slot before has
+ * finished; the compute stream waits once, at the layer's entry, for that transfer.  Layers
+ * 0 .. n_resident-1 are taken to be in slots 0 .. n_resident-1 already (the paper keeps the
+ * first MoE layer's experts resident), laid out as moe_prefill_layers_streamed lays them out:
+ * [w_gate][w_up][w_down][s_gate][s_up][s_down], each part aligned to 256 bytes.
+ * Every layer reads the same x and writes its own out (what links two MoE blocks in a model,
+ * attention and the residual path, is outside this block).  Nothing is synchronised with the
+ * host; the call enqueues all layers and returns. */
+typedef struct moe_stream_layer {
+    const void *w_gate, *w_up, *w_down;   /* pinned HOST memory, w_dtype, [E,I,H] / [E,H,I] */
+    const float *s_gate, *s_up, *s_down;  /* pinned HOST memory, FP8 only, else NULL */
+    const float *w_router, *bias;         /* DEVICE memory ([E,H]; [E] or NULL): small, kept resident */
+    void *out;                            /* DEVICE memory [T,H], out_dtype */
+} moe_stream_layer_t;
+
+int32_t moe_layer_weight_bytes(const moe_config_t *cfg, size_t *bytes_out);
+
+/* slots: n_slots device buffers (256-byte aligned).  slot_events: 2*n_slots hipEvent_t (as
+ * void*) owned by the caller, used as "transfer landed" / "slot free" marks.  layer_events: NULL,
+ * or 2*n_layers hipEvent_t with timing enabled; [2i] is recorded on the compute stream before
+ * layer i's entry wait and [2i+1] after its last kernel, so their distance is the layer's wall
+ * time including any stall on the transfer (the t_c / t_e of App. B.4).  compute_stream and
+ * copy_stream must differ.  ws: moe_workspace_bytes(cfg, MOE_CALL_PREFILL_LAYER). */
+int32_t moe_prefill_layers_streamed(const moe_config_t *cfg, int32_t n_layers,
+                                    const moe_stream_layer_t *layers, const void *x,
+                                    void *const *slots, int32_t n_slots, int32_t n_resident,
+                                    void *const *slot_events, void *const *layer_events, void *ws,
+                                    size_t ws_bytes, void *compute_stream, void *copy_stream);
+
+/* f_tok of this block: counted flop per token, K*6*H*I + 2*H*E. */
+double moe_layer_flops_per_token(const moe_config_t *cfg);
+/* Eq. 1: T = t_EP * F_GPU * gamma (flop a batch must carry for its compute to cover the slowest
+ * per-layer transfer). */
+double moe_saturation_threshold_flops(double t_ep_seconds, double f_gpu_flops, double gamma);
+/* App. B.4, Eq. 3: T = gamma * (t_e / t_c) * C_dummy, with t_c the wall time of the resident
+ * first layer, t_e the largest wall time of a later layer and C_dummy = f_tok * n_ref; it
+ * collapses to gamma * C_dummy when t_e <= t_c, which is also the fallback when t_c is not
+ * positive (no calibration yet). */
+double moe_calibrated_threshold_flops(double t_c, double t_e, double c_dummy_flops, double gamma);
+
 #ifdef __cplusplus
 }
 #endif

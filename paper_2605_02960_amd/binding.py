@@ -17,6 +17,8 @@ KERNEL_ROUTER_GEMM, KERNEL_TOPK, KERNEL_PERMUTE, KERNEL_GATE_UP, KERNEL_DOWN, KE
 KERNEL_NAMES = ("router_gemm", "topk", "permute", "gate_up", "down", "combine")
 
 EXPORTED_SYMBOLS = (
+    "moe_layer_weight_bytes", "moe_prefill_layers_streamed", "moe_layer_flops_per_token",
+    "moe_saturation_threshold_flops", "moe_calibrated_threshold_flops",
     "moe_abi_version", "moe_status_string", "moe_set_profile_events", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
 )
@@ -31,6 +33,11 @@ class MoEError(RuntimeError):
 class MoEConfig(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("T", "H", "E", "K", "I", "x_dtype", "w_dtype", "out_dtype", "flags")]
+
+
+class MoEStreamLayer(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("w_gate", "w_up", "w_down", "s_gate", "s_up", "s_down", "w_router", "bias", "out")]
 
 
 class MoETaps(ctypes.Structure):
@@ -73,8 +80,50 @@ def lib():
         L.moe_combine.argtypes = [cfgp] + [vp] * 5
         L.moe_prefill_layer.restype = i32
         L.moe_prefill_layer.argtypes = [cfgp] + [vp] * 10 + [ctypes.POINTER(MoETaps), vp, sz, vp]
+        L.moe_layer_weight_bytes.restype = i32
+        L.moe_layer_weight_bytes.argtypes = [cfgp, ctypes.POINTER(sz)]
+        L.moe_prefill_layers_streamed.restype = i32
+        L.moe_prefill_layers_streamed.argtypes = [cfgp, i32, ctypes.POINTER(MoEStreamLayer), vp,
+                                                  ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp),
+                                                  ctypes.POINTER(vp), vp, sz, vp, vp]
+        f64 = ctypes.c_double
+        L.moe_layer_flops_per_token.restype = f64
+        L.moe_layer_flops_per_token.argtypes = [cfgp]
+        L.moe_saturation_threshold_flops.restype = f64
+        L.moe_saturation_threshold_flops.argtypes = [f64, f64, f64]
+        L.moe_calibrated_threshold_flops.restype = f64
+        L.moe_calibrated_threshold_flops.argtypes = [f64, f64, f64, f64]
         _lib = L
     return _lib
+
+
+class HipEvents:
+    """Raw hipEvent_t handles through the HIP runtime that torch has loaded (plumbing for the
+    calls that take events: timing brackets and the streaming ring)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(e)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return e.value
+
+    def elapsed_ms(self, a, b):
+        if self.hip.hipEventSynchronize(b) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+        ms = ctypes.c_float()
+        if self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value
+
+    def destroy(self, e):
+        self.hip.hipEventDestroy(e)
 
 
 # ------------------------------------------------------------------ helpers
@@ -191,6 +240,58 @@ def moe_combine(cfg, y_perm, inv_perm, topk_w, out=None, stream=None):
     _check(lib().moe_combine(ctypes.byref(cfg), _p(y_perm), _p(inv_perm), _p(topk_w), _p(out),
                              _stream(stream)), "moe_combine")
     return out
+
+
+def moe_layer_weight_bytes(cfg):
+    n = ctypes.c_size_t(0)
+    _check(lib().moe_layer_weight_bytes(ctypes.byref(cfg), ctypes.byref(n)), "moe_layer_weight_bytes")
+    return n.value
+
+
+def moe_layer_flops_per_token(cfg):
+    return lib().moe_layer_flops_per_token(ctypes.byref(cfg))
+
+
+def moe_saturation_threshold_flops(t_ep_seconds, f_gpu_flops, gamma=1.2):
+    return lib().moe_saturation_threshold_flops(t_ep_seconds, f_gpu_flops, gamma)
+
+
+def moe_calibrated_threshold_flops(t_c, t_e, c_dummy_flops, gamma=1.2):
+    return lib().moe_calibrated_threshold_flops(t_c, t_e, c_dummy_flops, gamma)
+
+
+def moe_prefill_layers_streamed(cfg, layers, x, slots, n_resident=0, ws=None, compute_stream=None,
+                                copy_stream=None, events=None, time_layers=False):
+    """layers: list of dicts; w_gate/w_up/w_down (and s_* for fp8) are PINNED HOST tensors, w_router /
+    bias / out device tensors.  slots: device uint8 tensors of moe_layer_weight_bytes(cfg).
+    Returns the list of (entry, exit) event handles per layer when time_layers, else None."""
+    dev = x.device
+    n = len(layers)
+    arr = (MoEStreamLayer * max(n, 1))()
+    for i, l in enumerate(layers):
+        for name in ("w_gate", "w_up", "w_down", "s_gate", "s_up", "s_down", "w_router", "bias", "out"):
+            ten = l.get(name)
+            setattr(arr[i], name, None if ten is None else ten.data_ptr())
+    events = events or HipEvents()
+    vp = ctypes.c_void_p
+    slot_ptrs = (vp * len(slots))(*[s.data_ptr() for s in slots])
+    slot_ev = (vp * (2 * len(slots)))(*[events.create() for _ in range(2 * len(slots))])
+    layer_ev = None
+    pairs = None
+    if time_layers:
+        handles = [events.create() for _ in range(2 * n)]
+        layer_ev = (vp * (2 * n))(*handles)
+        pairs = [(handles[2 * i], handles[2 * i + 1]) for i in range(n)]
+    if ws is None:
+        ws, nb = _ws(cfg, CALL_PREFILL_LAYER, dev)
+    else:
+        nb = ws.numel()
+    cs = torch.cuda.current_stream() if compute_stream is None else compute_stream
+    ps = torch.cuda.Stream() if copy_stream is None else copy_stream
+    _check(lib().moe_prefill_layers_streamed(ctypes.byref(cfg), n, arr, _p(x), slot_ptrs, len(slots), n_resident,
+                                             slot_ev, layer_ev, _p(ws), nb, ctypes.c_void_p(cs.cuda_stream),
+                                             ctypes.c_void_p(ps.cuda_stream)), "moe_prefill_layers_streamed")
+    return pairs
 
 
 def moe_prefill_layer(cfg, x, w_router, bias, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down=None,

@@ -1,19 +1,23 @@
-// Grouped SwiGLU expert FFN on the gfx950 matrix cores (bf16 x bf16 -> f32 MFMA): the ragged
-// per-expert GEMMs of Sec. 4.2 of the paper, run with every expert of the layer resident
-// (Sec. 6.2).  Two launches over the device-built tile tables:
+// Grouped SwiGLU expert FFN on the gfx950 matrix cores (bf16 or fp8 operands, f32 accumulate):
+// the ragged per-expert GEMMs of Sec. 4.2 of the paper, run with every expert of the layer
+// resident (Sec. 6.2).  Two launches over the device-built tile tables:
 //   gate/up : act[p, i]  = SiLU(x_p . Wg_e[i,:]) * (x_p . Wu_e[i,:])   rounded once to bf16
 //   down    : y[p, h]    = act[p,:] . Wd_e[h,:]                          float32
 // Rows of x are gathered through perm while the token tile is loaded (no permuted copy of x).
 //
 // Tiling.  Workgroup = 512 threads = 8 waves (4 along rows x 2 along columns), tile 256 rows x
-// 256 weight rows x 64 (K).  For gate/up the 256 weight rows are 128 rows of Wg and the same
-// 128 rows of Wu, so that a lane holds g and u of one output element side by side.  Each wave
-// owns 64 rows x 128 weight rows = 2 x 4 MFMA 32x32x16 blocks (128 accumulator registers).
+// 256 weight rows x one K step of 128 bytes per row (64 bf16 or 128 fp8).  For gate/up the 256
+// weight rows are 128 rows of Wg and the same 128 rows of Wu, so that a lane holds g and u of one
+// output element side by side.  Each wave owns 64 rows x 128 weight rows = 2 x 4 MFMA blocks of
+// 32 x 32 (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x64_f8f6f4; 128 accumulator registers).
 // The token fragment is the MFMA "A" operand and the weight fragment the "B" operand; the
 // wave's weight rows are interleaved over its output columns so that a lane ends up with 2
 // (gate/up) or 4 (down) adjacent output columns and 32 lanes store whole 128-byte lines.
 //
-// LDS.  A tile is [256 rows][64 bf16] = 128 bytes per row in 8 chunks of 16 bytes; chunk c of
+// fp8 (e4m3 codes, float scales per token row and per output channel): the accumulators hold sums
+// of code products and the scales are applied in the epilogue.
+//
+// LDS.  A tile is [256 rows][128 bytes] in 8 chunks of 16 bytes per row; chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which makes both the 16-byte stores of the loader
 // and the 16-byte fragment reads of the MFMA operands free of bank conflicts.  Two stages
 // (2 x 64 KB) are double-buffered with one barrier per K step.

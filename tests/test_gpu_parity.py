@@ -255,11 +255,11 @@ def test_qwen3_layer_8k_tokens():
     assert torch.equal(_fused(cfg, g), r["out"])
 
 
-def test_qwen3_layer_64k_tokens_zipf():
-    """Full size of the bench workload (T=65536, Zipf-like expert popularity), same launch
-    configuration as bench.py: integer outputs in full, sampled tokens for the floats, plus
-    properties that hold at any size."""
-    w = workloads.QWEN3_64K_ZIPF
+@pytest.mark.parametrize("w", [workloads.QWEN3_64K_ZIPF, workloads.QWEN3_30B_64K_ZIPF], ids=lambda w: w.name)
+def test_full_size_layer_64k_tokens_zipf(w):
+    """Full size of the bench workloads (T=65536, Zipf-like expert popularity; the 235B-A22B
+    layer shape and the 30B-A3B one), same launch configuration as bench.py: integer outputs in
+    full, sampled tokens for the floats, plus properties that hold at any size."""
     d = workloads.generate(w)
     g = gu.upload(d)
     cfg = gu.config_for(w)

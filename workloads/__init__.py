@@ -43,9 +43,13 @@ TINY = MoEWorkload("tiny_fp32", 1, 256, 256, 8, 2, 512, "fp32")
 QWEN3_8K = MoEWorkload("qwen3_235b_T8192_bf16", 2, 8192, 4096, 128, 8, 1536, "bf16")
 QWEN3_64K_ZIPF = MoEWorkload("qwen3_235b_T65536_bf16_zipf", 3, 65536, 4096, 128, 8, 1536, "bf16", True)
 QWEN3_32K_FP8 = MoEWorkload("qwen3_235b_T32768_fp8", 4, 32768, 4096, 128, 8, 1536, "fp8")
+# Second shape: the 30B-A3B sibling of the same model family (the model behind the paper's
+# motivation figures, Sec. 3); its dimensions come from the public model configuration:
+# hidden 2048, expert intermediate 768, 128 experts, top-8.
+QWEN3_30B_64K_ZIPF = MoEWorkload("qwen3_30b_a3b_T65536_bf16_zipf", 6, 65536, 2048, 128, 8, 768, "bf16", True)
 SWEEP_T = (512, 1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072)
 
-CONFIGS = {w.name: w for w in (TINY, QWEN3_8K, QWEN3_64K_ZIPF, QWEN3_32K_FP8)}
+CONFIGS = {w.name: w for w in (TINY, QWEN3_8K, QWEN3_64K_ZIPF, QWEN3_32K_FP8, QWEN3_30B_64K_ZIPF)}
 
 
 def sweep_point(T):
@@ -119,3 +123,26 @@ def generate(w, seed=0, threads=None):
         list(ex.map(fill_e, range(w.E)))
     out.update(x=x, w_gate=wg, w_up=wu, w_down=wd)
     return out
+
+
+def generate_requests(n_requests, n_prefixes, seed=0, *, n_roots=4, root_len=(256, 1024),
+                      tail_len=(64, 2048), suffix_len=(16, 512), zipf_s=1.1, vocab=32000):
+    """A prefix-sharing request stream for the frontend's scheduling round (Sec. 7; the
+    stand-in for the prefix-sharing evaluation sets of Sec. 8.1, which are not used).
+
+    n_prefixes distinct prompts' prefixes, each one of n_roots shared roots followed by its own
+    tail (so two prefixes under one root share the root's blocks only); every request draws its
+    prefix with Zipf(zipf_s) popularity and a suffix length uniformly from suffix_len.  Lengths
+    are not multiples of the block size on purpose.  Returns a list of
+    (prefix_tokens int32 array, suffix_len int) in arrival order."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([BASE_SEED, 7, seed])))
+    roots = [rng.integers(0, vocab, size=int(rng.integers(root_len[0], root_len[1] + 1)), dtype=np.int32)
+             for _ in range(n_roots)]
+    prefixes = []
+    for j in range(n_prefixes):
+        tail = rng.integers(0, vocab, size=int(rng.integers(tail_len[0], tail_len[1] + 1)), dtype=np.int32)
+        prefixes.append(np.concatenate([roots[j % n_roots], tail]))
+    p = 1.0 / np.arange(1, n_prefixes + 1, dtype=np.float64) ** zipf_s
+    pick = rng.choice(n_prefixes, size=n_requests, p=p / p.sum())
+    sfx = rng.integers(suffix_len[0], suffix_len[1] + 1, size=n_requests)
+    return [(prefixes[int(j)], int(s)) for j, s in zip(pick, sfx)]

@@ -1,5 +1,6 @@
 """MI355X-native MoE prefill block (router, top-k, grouping, grouped SwiGLU expert FFN,
-combine) behind a C ABI; see include/moe_prefill.h.  This package is the thin Python
+combine) behind a C ABI; see include/moe_prefill.h
+(and include/moe_sched.h for the host-only scheduling round).  This package is the thin Python
 binding: it marshals torch device tensors into the library's entry points and does no
 arithmetic of its own.  Importing it does not load the library; the first call does, and
 raises if libmoeprefill.so has not been built (python -m paper_2605_02960_amd.build)."""
@@ -13,4 +14,6 @@ from .binding import (  # noqa: F401
     moe_prefill_layer, make_config, EXPORTED_SYMBOLS, HipEvents, MoEStreamLayer,
     moe_layer_weight_bytes, moe_prefill_layers_streamed, moe_layer_flops_per_token,
     moe_saturation_threshold_flops, moe_calibrated_threshold_flops,
+    MoECostModel, moe_sched_create, moe_sched_destroy, moe_sched_hash_blocks, moe_sched_round,
+    moe_sched_blocks_stored, moe_sched_blocks_evicted, moe_sched_table_size,
 )

@@ -4,6 +4,7 @@ runs inside the library's HIP kernels."""
 import ctypes
 import os
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -21,6 +22,8 @@ EXPORTED_SYMBOLS = (
     "moe_saturation_threshold_flops", "moe_calibrated_threshold_flops",
     "moe_abi_version", "moe_status_string", "moe_set_profile_events", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
+    "moe_sched_create", "moe_sched_destroy", "moe_sched_hash_blocks", "moe_sched_round",
+    "moe_sched_blocks_stored", "moe_sched_blocks_evicted", "moe_sched_table_size",
 )
 
 
@@ -38,6 +41,10 @@ class MoEConfig(ctypes.Structure):
 class MoEStreamLayer(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("w_gate", "w_up", "w_down", "s_gate", "s_up", "s_down", "w_router", "bias", "out")]
+
+
+class MoECostModel(ctypes.Structure):
+    _fields_ = [("f_tok", ctypes.c_double), ("f_attn", ctypes.c_double)]
 
 
 class MoETaps(ctypes.Structure):
@@ -93,6 +100,20 @@ def lib():
         L.moe_saturation_threshold_flops.argtypes = [f64, f64, f64]
         L.moe_calibrated_threshold_flops.restype = f64
         L.moe_calibrated_threshold_flops.argtypes = [f64, f64, f64, f64]
+        L.moe_sched_create.restype = i32
+        L.moe_sched_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
+        L.moe_sched_destroy.restype = None
+        L.moe_sched_destroy.argtypes = [vp]
+        L.moe_sched_hash_blocks.restype = i32
+        L.moe_sched_hash_blocks.argtypes = [vp, i64, i32, vp]
+        L.moe_sched_round.restype = i32
+        L.moe_sched_round.argtypes = [vp, ctypes.POINTER(MoECostModel), f64, i64] + [vp] * 8 + [ctypes.POINTER(i64)]
+        L.moe_sched_blocks_stored.restype = i32
+        L.moe_sched_blocks_stored.argtypes = [vp, i32, vp, i64]
+        L.moe_sched_blocks_evicted.restype = i32
+        L.moe_sched_blocks_evicted.argtypes = [vp, i32, vp, i64]
+        L.moe_sched_table_size.restype = i32
+        L.moe_sched_table_size.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         _lib = L
     return _lib
 
@@ -314,3 +335,64 @@ def moe_prefill_layer(cfg, x, w_router, bias, w_gate, w_up, w_down, s_gate=None,
                                    _p(w_down), _p(s_gate), _p(s_up), _p(s_down), _p(out), tp, _p(ws), n,
                                    _stream(stream)), "moe_prefill_layer")
     return out
+
+
+# ------------------------------------------------------------------ scheduling round (host only; numpy arrays)
+def _np(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, ctypes.c_void_p(a.ctypes.data if a.size else None)
+
+
+def moe_sched_create(n_workers, block_tokens):
+    h = ctypes.c_void_p()
+    _check(lib().moe_sched_create(n_workers, block_tokens, ctypes.byref(h)), "moe_sched_create")
+    return h
+
+
+def moe_sched_destroy(handle):
+    lib().moe_sched_destroy(handle)
+
+
+def moe_sched_hash_blocks(tokens, block_tokens):
+    tokens, tp = _np(tokens, np.int32)
+    out = np.empty(max(tokens.size // block_tokens, 0), dtype=np.uint64)
+    _check(lib().moe_sched_hash_blocks(tp, tokens.size, block_tokens,
+                                       ctypes.c_void_p(out.ctypes.data if out.size else None)), "moe_sched_hash_blocks")
+    return out
+
+
+def moe_sched_round(handle, f_tok, f_attn, threshold, block_hashes, hash_offsets, prefix_tokens, suffix_tokens, loads):
+    """loads (float64 [n_workers]) is updated in place.  Returns (assigned, matched_tokens, delta, n_assigned)."""
+    hashes, hp = _np(block_hashes, np.uint64)
+    offs, op = _np(hash_offsets, np.int64)
+    P, pp = _np(prefix_tokens, np.int64)
+    S, sp = _np(suffix_tokens, np.int64)
+    if not (isinstance(loads, np.ndarray) and loads.dtype == np.float64 and loads.flags.c_contiguous):
+        raise TypeError("loads must be a contiguous float64 numpy array (it is updated in place)")
+    n = P.size
+    assigned = np.empty(n, dtype=np.int32)
+    matched = np.empty(n, dtype=np.int64)
+    delta = np.empty(n, dtype=np.float64)
+    done = ctypes.c_int64(0)
+    cost = MoECostModel(float(f_tok), float(f_attn))
+    _check(lib().moe_sched_round(handle, ctypes.byref(cost), float(threshold), n, hp, op, pp, sp,
+                                 ctypes.c_void_p(loads.ctypes.data), ctypes.c_void_p(assigned.ctypes.data if n else None),
+                                 ctypes.c_void_p(matched.ctypes.data if n else None),
+                                 ctypes.c_void_p(delta.ctypes.data if n else None), ctypes.byref(done)), "moe_sched_round")
+    return assigned, matched, delta, done.value
+
+
+def moe_sched_blocks_stored(handle, worker, hashes):
+    h, hp = _np(hashes, np.uint64)
+    _check(lib().moe_sched_blocks_stored(handle, worker, hp, h.size), "moe_sched_blocks_stored")
+
+
+def moe_sched_blocks_evicted(handle, worker, hashes):
+    h, hp = _np(hashes, np.uint64)
+    _check(lib().moe_sched_blocks_evicted(handle, worker, hp, h.size), "moe_sched_blocks_evicted")
+
+
+def moe_sched_table_size(handle, worker):
+    c, p = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().moe_sched_table_size(handle, worker, ctypes.byref(c), ctypes.byref(p)), "moe_sched_table_size")
+    return c.value, p.value

@@ -20,7 +20,7 @@ def L():
 
 
 def header_functions():
-    src = open(os.path.join(ROOT, "include", "moe_prefill.h")).read()
+    src = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("moe_prefill.h", "moe_sched.h"))
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src)))
 

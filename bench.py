@@ -24,8 +24,8 @@ PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0, "fp32": 157.3}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen3_235b_T65536_bf16_zipf",
                     help="a name from workloads.CONFIGS, or sweep:<T> for the uniform-routing sweep point")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -6,28 +6,41 @@
 
 namespace moe {
 
-template <bool OUT_BF16>
-__global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__ y, int row_vec,
+// KC > 0: K is the compile-time constant KC (slot loop unrolled, all KC row reads of a chunk in
+// flight together); KC = 0: any K.  The token's positions and weights are wave-uniform, so they
+// are fetched through the scalar path.
+template <bool OUT_BF16, int KC>
+__global__ __launch_bounds__(256) void combine_kernel(const f32x4* __restrict__ y, int row_vec,
                                                      const int32_t* __restrict__ inv_perm,
-                                                     const float* __restrict__ w, int K,
+                                                     const float* __restrict__ w, int K_any,
                                                      void* __restrict__ out) {
-    __shared__ int32_t pos[32];
-    __shared__ float wt[32];
     const int t = blockIdx.x;
-    if (threadIdx.x < K) {
-        pos[threadIdx.x] = inv_perm[(size_t)t * K + threadIdx.x];
-        wt[threadIdx.x] = w[(size_t)t * K + threadIdx.x];
-    }
-    __syncthreads();
+    const int K = KC > 0 ? KC : K_any;
+    const int32_t* __restrict__ pos = inv_perm + (size_t)t * K;
+    const float* __restrict__ wt = w + (size_t)t * K;
     for (int i = threadIdx.x; i < row_vec; i += blockDim.x) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int j = 0; j < K; ++j) {
-            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(y + (size_t)pos[j] * row_vec + i));
-            const float s = wt[j];
-            acc.x = fmaf(s, v.x, acc.x);
-            acc.y = fmaf(s, v.y, acc.y);
-            acc.z = fmaf(s, v.z, acc.z);
-            acc.w = fmaf(s, v.w, acc.w);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (KC > 0) {
+            f32x4 v[KC];
+#pragma unroll
+            for (int j = 0; j < KC; ++j) v[j] = __builtin_nontemporal_load(y + (size_t)pos[j] * row_vec + i);
+#pragma unroll
+            for (int j = 0; j < KC; ++j) {
+                const float s = wt[j];
+                acc.x = fmaf(s, v[j].x, acc.x);
+                acc.y = fmaf(s, v[j].y, acc.y);
+                acc.z = fmaf(s, v[j].z, acc.z);
+                acc.w = fmaf(s, v[j].w, acc.w);
+            }
+        } else {
+            for (int j = 0; j < K; ++j) {
+                const f32x4 v = __builtin_nontemporal_load(y + (size_t)pos[j] * row_vec + i);
+                const float s = wt[j];
+                acc.x = fmaf(s, v.x, acc.x);
+                acc.y = fmaf(s, v.y, acc.y);
+                acc.z = fmaf(s, v.z, acc.z);
+                acc.w = fmaf(s, v.w, acc.w);
+            }
         }
         if constexpr (OUT_BF16) {
             uint2 o;
@@ -35,7 +48,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__
             o.y = (uint32_t)f32_to_bf16_bits(acc.z) | ((uint32_t)f32_to_bf16_bits(acc.w) << 16);
             static_cast<uint2*>(out)[(size_t)t * row_vec + i] = o;
         } else {
-            static_cast<float4*>(out)[(size_t)t * row_vec + i] = acc;
+            static_cast<f32x4*>(out)[(size_t)t * row_vec + i] = acc;
         }
     }
 }
@@ -65,9 +78,15 @@ int32_t launch_combine(const moe_config_t& c, const float* y_perm, const int32_t
     KernelBracket kb(MOE_KERNEL_COMBINE, s);
     const bool vec = (c.H % 4 == 0) && ((uintptr_t)y_perm % 16 == 0) && ((uintptr_t)out % 16 == 0);
     if (vec) {
-        const float4* y = reinterpret_cast<const float4*>(y_perm);
-        if (bf) combine_kernel<true><<<c.T, 256, 0, s>>>(y, c.H / 4, inv_perm, topk_w, c.K, out);
-        else combine_kernel<false><<<c.T, 256, 0, s>>>(y, c.H / 4, inv_perm, topk_w, c.K, out);
+        const f32x4* y = reinterpret_cast<const f32x4*>(y_perm);
+#define MOE_COMBINE_LAUNCH(KC_)                                                                      \
+    if (bf) combine_kernel<true, KC_><<<c.T, 256, 0, s>>>(y, c.H / 4, inv_perm, topk_w, c.K, out);   \
+    else combine_kernel<false, KC_><<<c.T, 256, 0, s>>>(y, c.H / 4, inv_perm, topk_w, c.K, out);
+        if (c.K == 8) { MOE_COMBINE_LAUNCH(8) }
+        else if (c.K == 4) { MOE_COMBINE_LAUNCH(4) }
+        else if (c.K == 2) { MOE_COMBINE_LAUNCH(2) }
+        else { MOE_COMBINE_LAUNCH(0) }
+#undef MOE_COMBINE_LAUNCH
     } else {
         if (bf) combine_scalar_kernel<true><<<c.T, 256, 0, s>>>(y_perm, c.H, inv_perm, topk_w, c.K, out);
         else combine_scalar_kernel<false><<<c.T, 256, 0, s>>>(y_perm, c.H, inv_perm, topk_w, c.K, out);

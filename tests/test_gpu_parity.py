@@ -283,6 +283,6 @@ def test_full_size_layer_64k_tokens_zipf(w):
     perm = r["perm"].cpu().numpy()
     off = r["offsets"].cpu().numpy()
     rare = perm[off[96]:off[128]] // w.K
-    tokens = np.unique(np.concatenate([rng.choice(w.T, size=96, replace=False), rare[:48]]))
+    tokens = np.unique(np.concatenate([rng.choice(w.T, size=2048, replace=False), rare[:64]]))
     _bf16_checks(w, d, g, cfg, r, info, tokens)
     assert torch.isfinite(out).all()

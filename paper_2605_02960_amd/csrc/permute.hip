@@ -43,40 +43,60 @@ __global__ __launch_bounds__(PERM_THREADS) void seg_hist_kernel(const int32_t* _
     for (int e = threadIdx.x; e < E; e += PERM_THREADS) seg_hist[(size_t)blockIdx.x * E + e] = h[e];
 }
 
-// One workgroup of 1024 threads.  Thread e walks down column e of seg_hist, turning it into
-// the exclusive prefix over segments; then the column totals are scanned over experts.
+// One workgroup of 1024 threads, C = 1024 / E' of them per expert column (E' = E rounded up to a
+// power of two): thread (c, e) owns a contiguous chunk of segments.  Chunk sums -> column totals
+// -> offsets over experts -> every thread rewrites its chunk as running positions.  All loads of
+// a chunk are independent of each other, so the walk is not a chain of memory latencies.
 __global__ __launch_bounds__(1024) void seg_scan_kernel(int32_t* __restrict__ seg_hist, int nseg,
                                                        int E, int32_t* __restrict__ counts,
                                                        int32_t* __restrict__ offsets) {
-    __shared__ int32_t tot[MAX_E];
+    __shared__ int32_t part[1024];        // chunk sums, [c][e] with row length EP
     __shared__ int32_t off[MAX_E + 1];
-    const int e = threadIdx.x;
-    int32_t run = 0;
+    int EP = 1;
+    while (EP < E) EP <<= 1;
+    const int C = 1024 / EP;              // chunks per column (>= 1 since E <= 1024)
+    const int e = threadIdx.x & (EP - 1), c = threadIdx.x / EP;
+    const int per = (nseg + C - 1) / C;
+    const int s0 = min(c * per, nseg), s1 = min(s0 + per, nseg);
+    int32_t sum = 0;
+    if (e < E)
+        for (int s = s0; s < s1; ++s) sum += seg_hist[(size_t)s * E + e];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    // exclusive scan over the chunks of a column (C <= 1024 / 1, short), column total in off[]
+    int32_t before = 0, total = 0;
     if (e < E) {
-        for (int s = 0; s < nseg; ++s) {
-            const int32_t v = seg_hist[(size_t)s * E + e];
-            seg_hist[(size_t)s * E + e] = run;
-            run += v;
+        for (int cc = 0; cc < C; ++cc) {
+            const int32_t v = part[cc * EP + e];
+            if (cc < c) before += v;
+            total += v;
         }
-        tot[e] = run;
     }
+    __syncthreads();
+    if (c == 0 && e < E) part[e] = total;   // column totals
     __syncthreads();
     if (threadIdx.x == 0) {
         int32_t acc = 0;
         for (int i = 0; i < E; ++i) {
             off[i] = acc;
-            acc += tot[i];
+            acc += part[i];
         }
         off[E] = acc;
     }
     __syncthreads();
     if (e < E) {
-        counts[e] = tot[e];
-        offsets[e] = off[e];
-        const int32_t o = off[e];
-        for (int s = 0; s < nseg; ++s) seg_hist[(size_t)s * E + e] += o;
+        if (c == 0) {
+            counts[e] = part[e];
+            offsets[e] = off[e];
+        }
+        int32_t run = off[e] + before;
+        for (int s = s0; s < s1; ++s) {
+            const int32_t v = seg_hist[(size_t)s * E + e];
+            seg_hist[(size_t)s * E + e] = run;
+            run += v;
+        }
     }
-    if (e == 0) offsets[E] = off[E];
+    if (threadIdx.x == 0) offsets[E] = off[E];
 }
 
 __global__ __launch_bounds__(PERM_THREADS) void seg_scatter_kernel(

@@ -48,7 +48,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const f32x4* __restrict__ 
             o.y = (uint32_t)f32_to_bf16_bits(acc.z) | ((uint32_t)f32_to_bf16_bits(acc.w) << 16);
             static_cast<uint2*>(out)[(size_t)t * row_vec + i] = o;
         } else {
-            static_cast<f32x4*>(out)[(size_t)t * row_vec + i] = acc;
+            // the output is larger than the caches and is not read again by this block
+            __builtin_nontemporal_store(acc, static_cast<f32x4*>(out) + (size_t)t * row_vec + i);
         }
     }
 }

@@ -77,7 +77,9 @@ typedef enum moe_call {
  *             weights are e4m3 codes with one float scale per output channel)
  *   out_dtype F32 or BF16 (the bf16 result is the float32 result rounded once)
  *   The BF16 path needs H % 128 == 0 and I % 128 == 0, the FP8 path H % 256 == 0 and
- *   I % 256 == 0; the F32 path takes any size.
+ *   I % 256 == 0; the F32 path takes any size.  The BF16 and FP8 paths also need
+ *   T*H*2 < 4 GiB (x is addressed with 32-bit byte offsets), H <= 65536 and I <= 32768;
+ *   larger shapes return MOE_ERR_UNSUPPORTED.
  */
 typedef struct moe_config {
     int32_t T, H, E, K, I;

@@ -104,10 +104,13 @@ __device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, i
     const size_t wbytes = (size_t)a.N * a.ldb_bytes;
     t.b0e = a.B0 + (size_t)e * wbytes;
     t.b1e = (MODE == MODE_GATE_UP) ? a.B1 + (size_t)e * wbytes : t.b0e;
+    // gate/up gathers rows of x (offsets from x itself, T*H*esz < 4 GiB); down reads the tile's own
+    // contiguous rows of act, so its offsets are taken from the tile's first row and stay small
+    // however many routed rows there are.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int r = min(t.row0 + lr + 64 * i, t.row_end - 1);      // rows past the group's end re-read its last row
-        const uint32_t src = a.perm ? (uint32_t)(a.perm[r] / a.kdiv) : (uint32_t)r;
+        const uint32_t src = (MODE == MODE_GATE_UP) ? (uint32_t)(a.perm[r] / a.kdiv) : (uint32_t)(r - t.row0);
         t.a_off[i] = src * a.lda_bytes + lc * 16;
     }
 }
@@ -284,8 +287,10 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #define MOE_GLOAD(SET_, CTX_, KT_)                                                        \
     {                                                                                     \
         const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                  \
+        const char* abase =                                                               \
+            (MODE == MODE_GATE_UP) ? a.A : a.A + (size_t)CTX_.row0 * a.lda_bytes;         \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                   \
-            ra##SET_[i] = *reinterpret_cast<const u32x4*>(a.A + (CTX_.a_off[i] + kb));    \
+            ra##SET_[i] = *reinterpret_cast<const u32x4*>(abase + (CTX_.a_off[i] + kb));  \
             rb##SET_[i] = *reinterpret_cast<const u32x4*>(                                \
                 ((i < 2 || MODE == MODE_DOWN) ? CTX_.b0e : CTX_.b1e) + (CTX_.b_off[i] + kb)); \
         }                                                                                 \
@@ -490,8 +495,8 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     // the K loop runs in pairs of 128-byte steps; 32-bit byte offsets are used on the load side;
     // column tiles are packed in 8 bits
     if (c.H % (2 * kstep) != 0 || c.I % (2 * kstep) != 0) return MOE_ERR_BAD_SHAPE;
-    if ((uint64_t)c.T * c.H * esz > 0xFFFFFFFFull || (uint64_t)P * c.I * esz > 0xFFFFFFFFull ||
-        (uint64_t)c.I * c.H * esz > 0xFFFFFFFFull || c.I > 128 * 256 || c.H > 256 * 256)
+    if ((uint64_t)c.T * c.H * esz > 0xFFFFFFFFull || (uint64_t)c.I * c.H * esz > 0xFFFFFFFFull ||
+        c.I > 128 * 256 || c.H > 256 * 256)
         return MOE_ERR_UNSUPPORTED;
 
     const FfnWs w = ffn_ws_layout(c);

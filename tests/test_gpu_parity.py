@@ -286,3 +286,34 @@ def test_full_size_layer_64k_tokens_zipf(w):
     tokens = np.unique(np.concatenate([rng.choice(w.T, size=2048, replace=False), rare[:64]]))
     _bf16_checks(w, d, g, cfg, r, info, tokens)
     assert torch.isfinite(out).all()
+
+
+def test_bf16_layer_with_more_than_4gib_of_activations():
+    """T = 196608 tokens at the 235B-A22B layer shape: 1.57 M routed rows, so the bf16 activation
+    matrix (4.8 GB) cannot be addressed with 32-bit byte offsets from its start.  Integer outputs
+    in full; floats on sampled tokens, among them tokens whose rows sit past the 4 GiB mark."""
+    w = workloads.scaled(workloads.QWEN3_8K, name="qwen3_235b_T196608_bf16", T=196608)
+    assert w.rows * w.I * 2 > 2 ** 32
+    d = workloads.generate(w)
+    g = gu.upload(d)
+    cfg = gu.config_for(w)
+    print(f"case {w.name}", flush=True)
+    taps = dict(logits=torch.empty((w.T, w.E), dtype=torch.float32, device=gu.DEV),
+                topk_idx=torch.empty((w.T, w.K), dtype=torch.int32, device=gu.DEV),
+                topk_w=torch.empty((w.T, w.K), dtype=torch.float32, device=gu.DEV),
+                counts=torch.empty((w.E,), dtype=torch.int32, device=gu.DEV),
+                offsets=torch.empty((w.E + 1,), dtype=torch.int32, device=gu.DEV),
+                perm=torch.empty((w.rows,), dtype=torch.int32, device=gu.DEV),
+                inv_perm=torch.empty((w.rows,), dtype=torch.int32, device=gu.DEV),
+                act=torch.empty((w.rows, w.I), dtype=torch.bfloat16, device=gu.DEV),
+                y_perm=torch.empty((w.rows, w.H), dtype=torch.float32, device=gu.DEV))
+    out = _fused(cfg, g, taps)
+    r = dict(taps, out=out)
+    info = gu.check_routing_and_grouping(cfg, d, r)
+    perm = r["perm"].cpu().numpy()
+    first_high = (2 ** 32) // (w.I * 2) + 1                   # first sorted row past 4 GiB
+    high = perm[first_high::4099][:96] // w.K
+    rng = np.random.default_rng(3)
+    tokens = np.unique(np.concatenate([rng.choice(w.T, size=160, replace=False), high]))
+    _bf16_checks(w, d, g, cfg, r, info, tokens)
+    assert torch.isfinite(out).all()

@@ -253,7 +253,7 @@ def stream_mode(a, np, torch, moe, workloads):
     fp8 = a.stream == "fp8"
     base = workloads.QWEN3_32K_FP8 if fp8 else workloads.QWEN3_8K
     tokens = [int(t) for t in a.stream_tokens.split(",")] if a.stream_tokens else \
-        ([32768, 131072, 262144] if fp8 else [16384, 65536, 131072])
+        ([32768, 131072, 262144] if fp8 else [16384, 65536, 131072, 262144, 393216])
 
     def up(v):
         if v is None:

@@ -57,7 +57,17 @@ typedef enum moe_dtype {
 } moe_dtype;
 
 enum { /* moe_config.flags */
-    MOE_FLAG_NONE = 0
+    MOE_FLAG_NONE = 0,
+    /* BF16 / FP8 paths: hand the float32 accumulators of the down projection to the combine as
+     * they are.  Without it every 16 adjacent columns of a y row share one power-of-two scale and
+     * are rounded to 16-bit codes: with amax the block's largest magnitude, k = biased float32
+     * exponent of amax (one higher when amax * 2^(141-k) >= 32767.5; at least 15), code =
+     * rint(v * 2^(141-k)), value = 2^(k-141) * code.  That halves the bytes between the two
+     * kernels; an element moves by at most 2^(k-142) <= amax/32768 (measured 1e-4 * rms on the
+     * layer output, against the 1e-2 * rms that rounding the activations to bf16 contributes).
+     * The float32 y that moe_grouped_ffn writes and the y_perm tap hold exactly these values.
+     * No effect on the F32 path. */
+    MOE_FLAG_Y_F32 = 1
 };
 
 typedef enum moe_call {
@@ -102,7 +112,8 @@ typedef struct moe_taps {
     void *act;           /* [P,I]   SwiGLU activations in sorted row order: F32 for the F32 path, else BF16 */
     uint8_t *act_q;      /* [P,I]   FP8 path only: e4m3 codes of act            */
     float *act_scale;    /* [P]     FP8 path only: per-row scales of act        */
-    float *y_perm;       /* [P,H]   expert outputs in sorted row order, F32     */
+    float *y_perm;       /* [P,H]   expert outputs in sorted row order, F32 (BF16 / FP8 paths: the
+                                    block-scaled values unless MOE_FLAG_Y_F32, see the flag) */
 } moe_taps_t;
 
 /* Kernels that moe_set_profile_events can bracket. */
@@ -175,7 +186,10 @@ int32_t moe_permute(const moe_config_t *cfg, const int32_t *topk_idx, const void
  *   x [T,H]; perm [P]; offsets [E+1]; w_gate,w_up [E,I,H]; w_down [E,H,I]
  *   (w_dtype; FP8: bytes); s_gate,s_up [E,I], s_down [E,H] F32 (FP8 only, else
  *   NULL); act_tap [P,I] or NULL (BF16, F32 on the F32 path); act_q_tap [P,I],
- *   act_scale_tap [P] or NULL (FP8 only); y_perm [P,H] F32. */
+ *   act_scale_tap [P] or NULL (FP8 only); y_perm [P,H] F32.  On the BF16 / FP8 paths y_perm
+ *   holds the block-scaled 16-bit values (exactly representable in F32) unless
+ *   MOE_FLAG_Y_F32 is set; moe_prefill_layer keeps y in the compact form itself when no
+ *   y_perm tap is asked for, with the same output bits. */
 int32_t moe_grouped_ffn(const moe_config_t *cfg, const void *x, const int32_t *perm,
                         const int32_t *offsets, const void *w_gate, const void *w_up,
                         const void *w_down, const float *s_gate, const float *s_up,

@@ -5,7 +5,7 @@ binding: it marshals torch device tensors into the library's entry points and do
 arithmetic of its own.  Importing it does not load the library; the first call does, and
 raises if libmoeprefill.so has not been built (python -m paper_2605_02960_amd.build)."""
 from .binding import (  # noqa: F401
-    MoEConfig, MoETaps, MoEError, DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3,
+    MoEConfig, MoETaps, MoEError, DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3, FLAG_Y_F32,
     CALL_ROUTE, CALL_PERMUTE, CALL_GROUPED_FFN, CALL_COMBINE, CALL_PREFILL_LAYER,
     KERNEL_ROUTER_GEMM, KERNEL_TOPK, KERNEL_PERMUTE, KERNEL_GATE_UP, KERNEL_DOWN, KERNEL_COMBINE,
     KERNEL_NAMES, moe_set_profile_events,

@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libmoeprefill.so")
 _lib = None
 
 DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3 = 0, 1, 2
+FLAG_Y_F32 = 1
 CALL_ROUTE, CALL_PERMUTE, CALL_GROUPED_FFN, CALL_COMBINE, CALL_PREFILL_LAYER = range(5)
 
 KERNEL_ROUTER_GEMM, KERNEL_TOPK, KERNEL_PERMUTE, KERNEL_GATE_UP, KERNEL_DOWN, KERNEL_COMBINE = range(6)

@@ -35,7 +35,7 @@ int32_t check_config(const moe_config_t* c) {
         default:
             return MOE_ERR_BAD_DTYPE;
     }
-    if (c->flags != 0) return MOE_ERR_UNSUPPORTED;
+    if ((c->flags & ~MOE_FLAG_Y_F32) != 0) return MOE_ERR_UNSUPPORTED;
     return MOE_OK;
 }
 
@@ -49,8 +49,12 @@ size_t ffn_ws(const moe_config_t& c) {
     return c.w_dtype == MOE_DTYPE_F32 ? ffn_f32_ws_bytes(c) : ffn_mfma_ws_bytes(c);
 }
 
+// The fused call keeps y in its compact form (16-bit codes + block scales) unless the
+// configuration asks for float32 or there is no compact form (F32 path).
+bool y_compact(const moe_config_t& c) { return c.w_dtype != MOE_DTYPE_F32 && !(c.flags & MOE_FLAG_Y_F32); }
+
 struct LayerWs {  // carve-up of the fused call's workspace
-    size_t logits, idx, w, counts, offsets, perm, inv, y, sub, total;
+    size_t logits, idx, w, counts, offsets, perm, inv, y, y_scales, sub, total;
 };
 LayerWs layer_ws(const moe_config_t& c) {
     const size_t P = (size_t)c.T * c.K;
@@ -64,7 +68,13 @@ LayerWs layer_ws(const moe_config_t& c) {
     l.offsets = take((size_t)(c.E + 1) * 4);
     l.perm = take(P * 4);
     l.inv = take(P * 4);
-    l.y = take(P * c.H * 4);
+    if (y_compact(c)) {   // a caller that wants to see y passes its own float32 buffer (taps.y_perm)
+        l.y = take(P * c.H * 2);
+        l.y_scales = take(P * (c.H / Y_BLOCK_COLS));
+    } else {
+        l.y = take(P * c.H * 4);
+        l.y_scales = l.y;
+    }
     size_t sub = permute_ws_bytes(c);
     if (ffn_ws(c) > sub) sub = ffn_ws(c);
     if (route_ws(c) > sub) sub = route_ws(c);
@@ -168,22 +178,27 @@ int32_t moe_permute(const moe_config_t* cfg, const int32_t* topk_idx, const void
     return MOE_OK;
 }
 
-int32_t moe_grouped_ffn(const moe_config_t* cfg, const void* x, const int32_t* perm,
-                        const int32_t* offsets, const void* w_gate, const void* w_up,
-                        const void* w_down, const float* s_gate, const float* s_up,
-                        const float* s_down, void* act_tap, uint8_t* act_q_tap,
-                        float* act_scale_tap, float* y_perm, void* ws, size_t ws_bytes,
-                        void* stream) {
+}  // extern "C"
+
+namespace {
+// moe_grouped_ffn, with y either as float32 (y_perm) or in its compact form (y_codes, y_scales).
+int32_t grouped_ffn(const moe_config_t* cfg, const void* x, const int32_t* perm,
+                    const int32_t* offsets, const void* w_gate, const void* w_up,
+                    const void* w_down, const float* s_gate, const float* s_up,
+                    const float* s_down, void* act_tap, uint8_t* act_q_tap,
+                    float* act_scale_tap, float* y_perm, int16_t* y_codes, uint8_t* y_scales,
+                    void* ws, size_t ws_bytes, void* stream) {
     int32_t st = check_config(cfg);
     if (st != MOE_OK) return st;
     const bool empty = cfg->T == 0;
-    if (!offsets || !w_gate || !w_up || !w_down || !ws || (!empty && (!x || !perm || !y_perm)))
+    if (!offsets || !w_gate || !w_up || !w_down || !ws ||
+        (!empty && (!x || !perm || (!y_perm && !(y_codes && y_scales)))))
         return MOE_ERR_NULL_PTR;
     if (cfg->w_dtype == MOE_DTYPE_FP8_E4M3 && (!s_gate || !s_up || !s_down)) return MOE_ERR_NULL_PTR;
     if (!aligned(ws, 256)) return MOE_ERR_UNALIGNED;
     if (cfg->w_dtype != MOE_DTYPE_F32 &&
         (!aligned(x, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(w_down, 16) ||
-         !aligned(y_perm, 16) || (act_tap && !aligned(act_tap, 16))))
+         !aligned(y_perm, 16) || !aligned(y_codes, 16) || (act_tap && !aligned(act_tap, 16))))
         return MOE_ERR_UNALIGNED;
     if (ws_bytes < ffn_ws(*cfg)) return MOE_ERR_WORKSPACE_TOO_SMALL;
     if (empty) return MOE_OK;
@@ -194,7 +209,21 @@ int32_t moe_grouped_ffn(const moe_config_t* cfg, const void* x, const int32_t* p
                               static_cast<const float*>(w_down), static_cast<float*>(act_tap), y_perm,
                               ws, s);
     return launch_ffn_mfma(*cfg, x, perm, offsets, w_gate, w_up, w_down, s_gate, s_up, s_down,
-                           act_tap, act_q_tap, act_scale_tap, y_perm, ws, s);
+                           act_tap, act_q_tap, act_scale_tap, y_perm, y_codes, y_scales, ws, s);
+}
+}  // namespace
+
+extern "C" {
+
+int32_t moe_grouped_ffn(const moe_config_t* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* w_gate, const void* w_up,
+                        const void* w_down, const float* s_gate, const float* s_up,
+                        const float* s_down, void* act_tap, uint8_t* act_q_tap,
+                        float* act_scale_tap, float* y_perm, void* ws, size_t ws_bytes,
+                        void* stream) {
+    if (cfg && cfg->T != 0 && !y_perm) return MOE_ERR_NULL_PTR;
+    return grouped_ffn(cfg, x, perm, offsets, w_gate, w_up, w_down, s_gate, s_up, s_down, act_tap,
+                       act_q_tap, act_scale_tap, y_perm, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int32_t moe_combine(const moe_config_t* cfg, const float* y_perm, const int32_t* inv_perm,
@@ -229,7 +258,10 @@ int32_t moe_prefill_layer(const moe_config_t* cfg, const void* x, const float* w
     int32_t* offsets = t.offsets ? t.offsets : reinterpret_cast<int32_t*>(w8 + l.offsets);
     int32_t* perm = t.perm ? t.perm : reinterpret_cast<int32_t*>(w8 + l.perm);
     int32_t* inv = t.inv_perm ? t.inv_perm : reinterpret_cast<int32_t*>(w8 + l.inv);
+    const bool compact = y_compact(*cfg) && !t.y_perm;
     float* y = t.y_perm ? t.y_perm : reinterpret_cast<float*>(w8 + l.y);
+    int16_t* y_codes = compact ? reinterpret_cast<int16_t*>(w8 + l.y) : nullptr;
+    uint8_t* y_scales = compact ? reinterpret_cast<uint8_t*>(w8 + l.y_scales) : nullptr;
     void* sub = w8 + l.sub;
     const size_t sub_bytes = l.total - l.sub;
 
@@ -237,9 +269,13 @@ int32_t moe_prefill_layer(const moe_config_t* cfg, const void* x, const float* w
     if (st != MOE_OK) return st;
     st = moe_permute(cfg, idx, nullptr, counts, offsets, perm, inv, nullptr, sub, sub_bytes, stream);
     if (st != MOE_OK) return st;
-    st = moe_grouped_ffn(cfg, x, perm, offsets, w_gate, w_up, w_down, s_gate, s_up, s_down, t.act,
-                         t.act_q, t.act_scale, y, sub, sub_bytes, stream);
+    st = grouped_ffn(cfg, x, perm, offsets, w_gate, w_up, w_down, s_gate, s_up, s_down, t.act, t.act_q,
+                     t.act_scale, compact ? nullptr : y, y_codes, y_scales, sub, sub_bytes, stream);
     if (st != MOE_OK) return st;
+    if (compact) {
+        if (empty) return MOE_OK;
+        return launch_combine_block16(*cfg, y_codes, y_scales, inv, tw, out, static_cast<hipStream_t>(stream));
+    }
     return moe_combine(cfg, y, inv, tw, out, stream);
 }
 

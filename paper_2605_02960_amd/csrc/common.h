@@ -97,12 +97,18 @@ size_t ffn_mfma_ws_bytes(const moe_config_t& c);
 int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* perm,
                         const int32_t* offsets, const void* wg, const void* wu, const void* wd,
                         const float* s_gate, const float* s_up, const float* s_down, void* act_tap,
-                        uint8_t* act_q_tap, float* act_scale_tap, float* y_perm, void* ws,
-                        hipStream_t s);
+                        uint8_t* act_q_tap, float* act_scale_tap, float* y_perm, int16_t* y_codes,
+                        uint8_t* y_exps, void* ws, hipStream_t s);
+// y in its compact form: 16-column blocks of int16 codes [P,H] with one exponent byte k each
+// [P,H/16], value = 2^(k-141) * code.  y_codes != NULL selects it (y_perm is then unused).
+constexpr int Y_BLOCK_COLS = 16;
 
 // ---- combine.hip
 int32_t launch_combine(const moe_config_t& c, const float* y_perm, const int32_t* inv_perm,
                        const float* topk_w, void* out, hipStream_t s);
+int32_t launch_combine_block16(const moe_config_t& c, const int16_t* y_codes, const uint8_t* y_exps,
+                               const int32_t* inv_perm, const float* topk_w, void* out,
+                               hipStream_t s);
 
 // ---- quant.hip
 int32_t launch_quantize_rows(const void* src_bf16, int64_t rows, int32_t cols, uint8_t* q,

@@ -55,6 +55,13 @@ constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * 256 * 4;   // + two buffers of 2
 constexpr int GROUP_ROWS = MOE_GROUP_ROWS, GROUP_COLS = MOE_GROUP_COLS;   // tile block one XCD works on at a time
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
+// How the down kernel hands y to the combine.  A y row is cut into blocks of 16 columns; a block
+// is stored as 16 int16 codes and one shared power-of-two scale (its exponent, one byte):
+// value = 2^(k - 141) * code.  That halves the bytes the two kernels move through HBM.
+enum { Y_EXACT_F32 = 0,      // float32 accumulators as they are
+       Y_BLOCK16_AS_F32 = 1, // the block-scaled values, written out as float32 (exactly representable)
+       Y_BLOCK16 = 2 };      // codes and exponents
+constexpr int Y_BLOCK = 16;
 
 struct MfmaArgs {
     const char* A;          // token-side operand: x [T,H] (gathered) or act [P,I], bf16
@@ -72,7 +79,9 @@ struct MfmaArgs {
     const int32_t* table;   // row tiles: [0] = count, then (expert, first row) pairs
     const int32_t* order;   // launch slot -> rt << 8 | ct
     const int32_t* offsets;
-    char* C;                // act [P,I] bf16 or y [P,H] f32
+    char* C;                // act [P,I] bf16, or y [P,H]: float32 (y_mode 0, 1) or int16 codes (y_mode 2)
+    uint8_t* Cs;            // y_mode 2: block exponents [P][N/16]
+    int32_t y_mode;         // down only, see Y_* below
     int32_t nct;            // column tiles
 };
 
@@ -159,24 +168,98 @@ __device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int lr
 // of f32 y) per store instruction.
 // fp8: the accumulators hold sums of code products; the float scales of the row and of the output
 // channel are applied here, in float32: value = acc * (s_row * s_channel).
+// max over the 4 lanes of a quad (DPP quad permutes: lane ^ 1, then lane ^ 2)
+__device__ __forceinline__ float quad_max(float v) {
+    int x = __float_as_int(v);
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false)));
+    x = __float_as_int(v);
+    return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false)));
+}
+
+// Down projection epilogue.  A lane holds 4 adjacent columns of a row per column range, the 4
+// lanes of a quad 16 adjacent columns: one storage block.  Block scale: with amax the block's
+// largest magnitude, k = biased exponent of amax (one higher if amax * 2^(141-k) would round to
+// 32768), at least 15; code = rint(v * 2^(141-k)), |code| <= 32767.  The rounding is the float32
+// addition of 1.5 * 2^23 (round to nearest even at integer spacing), fused with the exact scaling.
+template <bool FP8, typename ACC>
+__device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+                                                const TileCtx& t, int wm, int wn, int fr, int fq,
+                                                const float* row_scale) {
+    constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN, VLEN = Blk<FP8>::VLEN;
+    constexpr int NGRP = NN / 4;                 // column ranges of 4*BE columns, 4 adjacent columns per lane
+    const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
+    if (nb >= a.N) return;                       // N is a multiple of 128: the whole wave is in or out
+    float sg[NN];
+#pragma unroll
+    for (int j = 0; j < NN; ++j)
+        sg[j] = FP8 ? a.sB0[(size_t)t.e * a.N + nb + (j >> 2) * (4 * BE) + 4 * fr + (j & 3)] : 1.f;
+    const int y_mode = a.y_mode;
+#pragma unroll
+    for (int mi = 0; mi < NM; ++mi) {
+#pragma unroll
+        for (int v = 0; v < VLEN; ++v) {
+            const int lrow = wm * 64 + mi * BE + (v >> 2) * 8 + fq * 4 + (v & 3);   // row inside the tile
+            const int m = t.row0 + lrow;
+            const bool live = m < t.row_end;     // the same for all lanes that share a row
+            const float sr = FP8 ? row_scale[lrow] : 1.f;
+#pragma unroll
+            for (int grp = 0; grp < NGRP; ++grp) {
+                float r[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    r[q] = acc[grp * 4 + q][mi][v];
+                    if (FP8) r[q] *= sr * sg[grp * 4 + q];
+                }
+                const int n = nb + grp * (4 * BE) + 4 * fr;
+                if (y_mode == Y_EXACT_F32) {
+                    if (!live) continue;
+                    f32x4 o = {r[0], r[1], r[2], r[3]};
+                    // y is read back (by the combine) only after gigabytes more have gone by: streaming store
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n));
+                    continue;
+                }
+                const float amax = quad_max(fmaxf(fmaxf(fabsf(r[0]), fabsf(r[1])), fmaxf(fabsf(r[2]), fabsf(r[3]))));
+                uint32_t kf = (__float_as_uint(amax) + 0x100u) & 0x7F800000u;   // k << 23
+                kf = max(kf, 15u << 23);
+                const float inv = __uint_as_float((268u << 23) - kf);           // 2^(141-k)
+                uint32_t c[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) c[q] = __float_as_uint(__builtin_fmaf(r[q], inv, 12582912.f));   // low 16 bits: the code
+                if (!live) continue;
+                if (y_mode == Y_BLOCK16_AS_F32) {
+                    const float sc = __uint_as_float(kf - (14u << 23));         // 2^(k-141)
+                    f32x4 o;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) o[q] = sc * (float)(int)(short)(c[q] & 0xFFFFu);
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n));
+                } else {
+                    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+                    u32x2 o = {(c[0] & 0xFFFFu) | (c[1] << 16), (c[2] & 0xFFFFu) | (c[3] << 16)};
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(reinterpret_cast<int16_t*>(a.C) + (size_t)m * a.N + n));
+                    if ((fr & 3) == 0) a.Cs[(size_t)m * (a.N / Y_BLOCK) + n / Y_BLOCK] = (uint8_t)(kf >> 23);
+                }
+            }
+        }
+    }
+}
+
 template <int MODE, bool FP8, typename ACC>
 __device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
                                            const TileCtx& t, int wm, int wn, int fr, int fq,
                                            const float* row_scale) {
-    constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN, VLEN = Blk<FP8>::VLEN;
-    constexpr int NBG = Blk<FP8>::NBG;
-    constexpr int NGRP = (MODE == MODE_GATE_UP) ? 1 : NN / 4;     // column ranges per wave
-    constexpr int NPER = (MODE == MODE_GATE_UP) ? NBG : 4;        // adjacent columns per lane and range
-#pragma unroll
-    for (int grp = 0; grp < NGRP; ++grp) {
-        const int n = (MODE == MODE_GATE_UP) ? t.n0 + wn * 64 + NBG * fr
-                                             : t.n0 + wn * 128 + grp * (4 * BE) + 4 * fr;
-        if (n >= a.N) continue;
+    if constexpr (MODE == MODE_DOWN) {
+        store_tile_down<FP8, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
+    } else {
+        constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, VLEN = Blk<FP8>::VLEN;
+        constexpr int NBG = Blk<FP8>::NBG;
+        constexpr int NPER = NBG;                                     // adjacent columns per lane
+        const int n = t.n0 + wn * 64 + NBG * fr;
+        if (n >= a.N) return;
         float sg[NPER], su[NPER];   // per-channel scales (fp8): gate or down, and up
 #pragma unroll
         for (int q = 0; q < NPER; ++q) {
             sg[q] = FP8 ? a.sB0[(size_t)t.e * a.N + n + q] : 1.f;
-            su[q] = (FP8 && MODE == MODE_GATE_UP) ? a.sB1[(size_t)t.e * a.N + n + q] : 1.f;
+            su[q] = FP8 ? a.sB1[(size_t)t.e * a.N + n + q] : 1.f;
         }
 #pragma unroll
         for (int mi = 0; mi < NM; ++mi) {
@@ -186,7 +269,7 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM
                 const int m = t.row0 + lrow;
                 if (m >= t.row_end) continue;
                 const float sr = FP8 ? row_scale[lrow] : 1.f;   // staged in LDS at the start of the tile
-                if (MODE == MODE_GATE_UP) {
+                {
                     uint16_t h[NPER];
 #pragma unroll
                     for (int q = 0; q < NPER; ++q) {
@@ -206,16 +289,6 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM
                         o.y = (uint32_t)h[NPER - 2] | ((uint32_t)h[NPER - 1] << 16);
                         *reinterpret_cast<uint2*>(dst) = o;
                     }
-                } else {
-                    float r[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        r[q] = acc[grp * 4 + q][mi][v];
-                        if (FP8) r[q] *= sr * sg[q];
-                    }
-                    f32x4 o = {r[0], r[1], r[2], r[3]};
-                    // y_perm is read back (by the combine) only after 8 GiB more have gone by: streaming store
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n));
                 }
             }
         }
@@ -484,8 +557,8 @@ size_t ffn_mfma_ws_bytes(const moe_config_t& c) { return ffn_ws_layout(c).total;
 int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* perm,
                         const int32_t* offsets, const void* wg, const void* wu, const void* wd,
                         const float* s_gate, const float* s_up, const float* s_down, void* act_tap,
-                        uint8_t* act_q_tap, float* act_scale_tap, float* y_perm, void* ws,
-                        hipStream_t s) {
+                        uint8_t* act_q_tap, float* act_scale_tap, float* y_perm, int16_t* y_codes,
+                        uint8_t* y_exps, void* ws, hipStream_t s) {
     const bool fp8 = c.w_dtype == MOE_DTYPE_FP8_E4M3;
     if (!fp8 && c.w_dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED;
     const int64_t P = (int64_t)c.T * c.K;
@@ -588,7 +661,17 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.table = table;
     d.order = order_dn;
     d.offsets = offsets;
-    d.C = reinterpret_cast<char*>(y_perm);
+    // y: block-scaled 16-bit codes for the fused call, the same values as float32 for a caller
+    // that wants to see y, or the untouched float32 accumulators when the configuration asks
+    if (y_codes) {
+        d.C = reinterpret_cast<char*>(y_codes);
+        d.Cs = y_exps;
+        d.y_mode = Y_BLOCK16;
+    } else {
+        d.C = reinterpret_cast<char*>(y_perm);
+        d.Cs = nullptr;
+        d.y_mode = (c.flags & MOE_FLAG_Y_F32) ? Y_EXACT_F32 : Y_BLOCK16_AS_F32;
+    }
     d.nct = nct_dn;
     {
         KernelBracket kb(MOE_KERNEL_DOWN, s);

@@ -23,10 +23,18 @@ def upload(d):
     return {k: to_dev(v) for k, v in d.items()}
 
 
-def config_for(w, out_dtype=moe.DTYPE_F32):
+def config_for(w, out_dtype=moe.DTYPE_F32, flags=0):
     xd = moe.DTYPE_F32 if w.dtype == "fp32" else moe.DTYPE_BF16
     wd = {"fp32": moe.DTYPE_F32, "bf16": moe.DTYPE_BF16, "fp8": moe.DTYPE_FP8_E4M3}[w.dtype]
-    return moe.make_config(w.T, w.H, w.E, w.K, w.I, xd, wd, out_dtype)
+    return moe.make_config(w.T, w.H, w.E, w.K, w.I, xd, wd, out_dtype, flags)
+
+
+def block16_half_step(y_ref):
+    """Largest error the block-scaled 16-bit storage of y may add to each element: half a code
+    step of the element's 16-column block, at most amax/32768 (see MOE_FLAG_Y_F32 in the header)."""
+    shp = y_ref.shape
+    b = np.abs(y_ref).reshape(-1, shp[-1] // 16, 16)
+    return np.repeat(b.max(axis=-1) / 32768.0, 16, axis=-1).reshape(shp)
 
 
 def rms(a):

@@ -49,7 +49,7 @@ def test_config_validation_and_workspace(L):
     bad = [
         (dict(K=0), -2), (dict(K=129), -2), (dict(K=33, E=64), -2), (dict(E=1025), -2), (dict(T=-1), -2),
         (dict(H=4032), -2), (dict(I=1472), -2), (dict(x_dtype=2), -3), (dict(w_dtype=7), -3),
-        (dict(w_dtype=moe.DTYPE_F32), -3), (dict(out_dtype=2), -3), (dict(flags=1), -6),
+        (dict(w_dtype=moe.DTYPE_F32), -3), (dict(out_dtype=2), -3), (dict(flags=2), -6), (dict(flags=5), -6),
         (dict(T=2 ** 28), -2),
     ]
     for change, want in bad:

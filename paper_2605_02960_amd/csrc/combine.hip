@@ -44,8 +44,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const f32x4* __restrict__ 
         }
         if constexpr (OUT_BF16) {
             uint2 o;
-            o.x = (uint32_t)f32_to_bf16_bits(acc.x) | ((uint32_t)f32_to_bf16_bits(acc.y) << 16);
-            o.y = (uint32_t)f32_to_bf16_bits(acc.z) | ((uint32_t)f32_to_bf16_bits(acc.w) << 16);
+            o.x = pack2_bf16(acc.x, acc.y);
+            o.y = pack2_bf16(acc.z, acc.w);
             static_cast<uint2*>(out)[(size_t)t * row_vec + i] = o;
         } else {
             // the output is larger than the caches and is not read again by this block
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void combine_block16_kernel(const u32x4* __res
             u32x4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                o[e] = (uint32_t)f32_to_bf16_bits(acc[2 * e]) | ((uint32_t)f32_to_bf16_bits(acc[2 * e + 1]) << 16);
+                o[e] = pack2_bf16(acc[2 * e], acc[2 * e + 1]);
             static_cast<u32x4*>(out)[(size_t)t * row_vec8 + i] = o;
         } else {
             f32x4* o = static_cast<f32x4*>(out) + ((size_t)t * row_vec8 + i) * 2;

@@ -270,7 +270,7 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM
                 if (m >= t.row_end) continue;
                 const float sr = FP8 ? row_scale[lrow] : 1.f;   // staged in LDS at the start of the tile
                 {
-                    uint16_t h[NPER];
+                    float h[NPER];
 #pragma unroll
                     for (int q = 0; q < NPER; ++q) {
                         float g = acc[q][mi][v], u = acc[NBG + q][mi][v];
@@ -278,15 +278,15 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM
                             g *= sr * sg[q];
                             u *= sr * su[q];
                         }
-                        h[q] = f32_to_bf16_bits(silu_mul(g, u));
+                        h[q] = silu_mul(g, u);
                     }
                     uint16_t* dst = reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N + n;
                     if (NPER == 2) {
-                        *reinterpret_cast<uint32_t*>(dst) = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                        *reinterpret_cast<uint32_t*>(dst) = pack2_bf16(h[0], h[1]);
                     } else {
                         uint2 o;
-                        o.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                        o.y = (uint32_t)h[NPER - 2] | ((uint32_t)h[NPER - 1] << 16);
+                        o.x = pack2_bf16(h[0], h[1]);
+                        o.y = pack2_bf16(h[NPER - 2], h[NPER - 1]);
                         *reinterpret_cast<uint2*>(dst) = o;
                     }
                 }

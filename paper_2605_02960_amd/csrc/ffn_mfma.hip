@@ -181,10 +181,10 @@ __device__ __forceinline__ float quad_max(float v) {
 // largest magnitude, k = biased exponent of amax (one higher if amax * 2^(141-k) would round to
 // 32768), at least 15; code = rint(v * 2^(141-k)), |code| <= 32767.  The rounding is the float32
 // addition of 1.5 * 2^23 (round to nearest even at integer spacing), fused with the exact scaling.
-template <bool FP8, typename ACC>
-__device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
-                                                const TileCtx& t, int wm, int wn, int fr, int fq,
-                                                const float* row_scale) {
+template <bool FP8, int y_mode, typename ACC>
+__device__ __forceinline__ void store_tile_down_as(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+                                                   const TileCtx& t, int wm, int wn, int fr, int fq,
+                                                   const float* row_scale) {
     constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN, VLEN = Blk<FP8>::VLEN;
     constexpr int NGRP = NN / 4;                 // column ranges of 4*BE columns, 4 adjacent columns per lane
     const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
@@ -193,7 +193,6 @@ __device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8
 #pragma unroll
     for (int j = 0; j < NN; ++j)
         sg[j] = FP8 ? a.sB0[(size_t)t.e * a.N + nb + (j >> 2) * (4 * BE) + 4 * fr + (j & 3)] : 1.f;
-    const int y_mode = a.y_mode;
 #pragma unroll
     for (int mi = 0; mi < NM; ++mi) {
 #pragma unroll
@@ -241,6 +240,16 @@ __device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8
             }
         }
     }
+}
+
+template <bool FP8, typename ACC>
+__device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+                                                const TileCtx& t, int wm, int wn, int fr, int fq,
+                                                const float* row_scale) {
+    // one copy of the unrolled epilogue per storage form, chosen once per tile
+    if (a.y_mode == Y_BLOCK16) store_tile_down_as<FP8, Y_BLOCK16, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
+    else if (a.y_mode == Y_BLOCK16_AS_F32) store_tile_down_as<FP8, Y_BLOCK16_AS_F32, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
+    else store_tile_down_as<FP8, Y_EXACT_F32, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
 }
 
 template <int MODE, bool FP8, typename ACC>

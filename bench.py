@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=6)
     ap.add_argument("--slots", type=int, default=2)
     ap.add_argument("--stream-tokens", type=str, default=None, help="comma-separated token counts for --stream")
+    ap.add_argument("--sched", action="store_true",
+                    help="host-only: throughput of the frontend's scheduling round (no GPU is used)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -56,6 +58,11 @@ def main():
     import paper_2605_02960_amd as moe
     from paper_2605_02960_amd import build as moe_build
     import workloads
+
+    if a.sched:
+        if not os.path.exists(moe.lib_path()):
+            moe_build.build()
+        return sched_mode(a, np, moe, workloads)
 
     if not os.path.exists(moe.lib_path()):
         moe_build.build()
@@ -186,6 +193,43 @@ def main():
             "tokens_per_s_experts_only": round(n / (c1 - c0), 2),
         }
     print(json.dumps(res))
+
+
+def sched_mode(a, np, moe, workloads):
+    """Scheduling round (App. A, Alg. 1) over a seeded prefix-sharing request stream: rounds of
+    2000 requests on 8 workers, every routed prefix reported stored after its round."""
+    B, N, per_round = 16, 8, 2000
+    reqs = workloads.generate_requests(20000, 400, seed=9)
+    t0 = time.perf_counter()
+    hashes = [moe.moe_sched_hash_blocks(p, B) for p, _ in reqs]
+    t_hash = time.perf_counter() - t0
+    f_tok, f_attn = 44.0e9, 3.0e6
+    h = moe.moe_sched_create(N, B)
+    t_round, assigned_total, queue = 0.0, 0, []
+    try:
+        for r0 in range(0, len(reqs), per_round):
+            queue = queue + list(range(r0, r0 + per_round))
+            hs = [hashes[q] for q in queue]
+            offs = np.zeros(len(queue) + 1, dtype=np.int64)
+            offs[1:] = np.cumsum([len(x) for x in hs])
+            flat = np.concatenate(hs)
+            P = np.array([len(reqs[q][0]) for q in queue], dtype=np.int64)
+            S = np.array([reqs[q][1] for q in queue], dtype=np.int64)
+            loads = np.zeros(N)
+            t0 = time.perf_counter()
+            assigned, _, _, n_done = moe.moe_sched_round(h, f_tok, f_attn, 2.0e16, flat, offs, P, S, loads)
+            t_round += time.perf_counter() - t0
+            assigned_total += n_done
+            for q, g in zip(queue[:n_done], assigned[:n_done]):
+                moe.moe_sched_blocks_stored(h, int(g), hashes[q])
+            queue = queue[n_done:]
+    finally:
+        moe.moe_sched_destroy(h)
+    print(json.dumps({"sched": True, "workers": N, "block_tokens": B, "requests": len(reqs),
+                      "assigned": assigned_total, "mean_prefix_tokens": float(np.mean([len(p) for p, _ in reqs])),
+                      "hash_us_per_request": round(t_hash / len(reqs) * 1e6, 2),
+                      "round_us_per_request": round(t_round / max(assigned_total, 1) * 1e6, 3),
+                      "requests_per_s": round(assigned_total / t_round, 0)}))
 
 
 def sweep(a, np, torch, moe, workloads):

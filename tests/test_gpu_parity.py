@@ -347,3 +347,28 @@ def test_y_block16_storage_is_the_quantiser_applied_to_the_float32_result():
     # default: compact y inside the fused call == float32 copy of the same values in the staged calls
     assert torch.equal(_fused(cfg16, g), r16["out"])
     assert gu.max_err_over_rms(r16["out"].cpu().numpy(), r32["out"].cpu().numpy()) <= 3e-4
+
+
+def _random_bf16_shape(seed):
+    rng = np.random.default_rng(1000 + seed)
+    H = 128 * int(rng.integers(1, 5))
+    I = 128 * int(rng.integers(1, 5))
+    E = int(rng.integers(1, 41))
+    K = int(rng.integers(1, min(E, 9) + 1))
+    T = int(rng.integers(1, 1400))
+    return T, H, E, K, I, bool(rng.integers(0, 2))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_bf16_random_small_shapes(seed):
+    """Seeded random shapes of the bf16 path (H, I multiples of 128; any T, E, K): every token
+    against the oracle, fused == staged, both storage forms of y."""
+    T, H, E, K, I, zipf = _random_bf16_shape(seed)
+    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name=f"bf16_rand{seed}_{T}_{H}_{E}_{K}_{I}", T=T, H=H, E=E, K=K, I=I,
+                         zipf_bias=zipf)
+    d, g, cfg, r, info = _layer_case(w)
+    _bf16_checks(w, d, g, cfg, r, info, None)
+    assert torch.equal(_fused(cfg, g), r["out"])
+    cfg32 = gu.config_for(w, flags=moe.FLAG_Y_F32)
+    o32 = _fused(cfg32, g)
+    assert gu.max_err_over_rms(r["out"].cpu().numpy(), o32.cpu().numpy()) <= 5e-4

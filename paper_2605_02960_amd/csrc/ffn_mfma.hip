@@ -2,7 +2,8 @@
 // the ragged per-expert GEMMs of Sec. 4.2 of the paper, run with every expert of the layer
 // resident (Sec. 6.2).  Two launches over the device-built tile tables:
 //   gate/up : act[p, i]  = SiLU(x_p . Wg_e[i,:]) * (x_p . Wu_e[i,:])   rounded once to bf16
-//   down    : y[p, h]    = act[p,:] . Wd_e[h,:]                          float32
+//   down    : y[p, h]    = act[p,:] . Wd_e[h,:]                          float32 accumulators, handed
+//             on as 16-bit block floating point (16 columns per shared exponent) or as float32
 // Rows of x are gathered through perm while the token tile is loaded (no permuted copy of x).
 //
 // Tiling.  Workgroup = 512 threads = 8 waves (4 along rows x 2 along columns), tile 256 rows x
@@ -21,6 +22,10 @@
 // row r sits at position c ^ ((r >> 1) & 7), which makes both the 16-byte stores of the loader
 // and the 16-byte fragment reads of the MFMA operands free of bank conflicts.  Two stages
 // (2 x 64 KB) are double-buffered with one barrier per K step.
+//
+// Issue order.  Inside a K step every MFMA is followed by at most one LDS fragment read, global
+// load or LDS store (scheduling group barriers), so that the matrix pipe is fed while the memory
+// operations of the next K slice and of the K steps ahead are issued in its shadow.
 //
 // Pipeline.  Global loads are full 128-byte lines per row (one K step of one row), staged in two
 // register sets: the tile for K step k+2 is requested while step k is multiplied, so every request

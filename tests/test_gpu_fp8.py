@@ -57,7 +57,7 @@ def _quantise_weights(g, cfg):
     return out
 
 
-def _fp8_case(w, tokens):
+def _fp8_case(w, tokens, gate_end_to_end=True):
     d = workloads.generate(w)
     g = gu.upload(d)
     cfg = gu.config_for(w)
@@ -106,10 +106,21 @@ def _fp8_case(w, tokens):
     # stage 4: whole layer
     out = r["out"].cpu().numpy()[tok]
     e_out = gu.max_err_over_rms(out, ref["out"])
-    print(f"  {w.name}: layer max|err|/rms vs quantising oracle {e_out:.3e}; down stage {e_down:.3e}; "
+    # stage 4b: the combine of the oracle's down projection on the device's own codes: what the
+    # layer must give once the quantisation decisions are taken as the device took them
+    out_own = np.einsum("tj,tjh->th", ref["topk_w"][tok], y_ref)
+    e_own = gu.max_err_over_rms(out, out_own)
+    print(f"  {w.name}: layer max|err|/rms vs quantising oracle {e_out:.3e} (vs the oracle continued from the "
+          f"device's own activation codes {e_own:.3e}); down stage {e_down:.3e}; "
           f"bf16 activations differing by one ulp {100 * flips:.4f}%", flush=True)
     assert e_down <= TOL_FP8_DOWN
-    assert e_out <= TOL_FP8
+    assert e_own <= TOL_FP8_DOWN
+    # A one-ulp difference of a bf16 activation can flip its e4m3 code (a 6-12 % step of that element);
+    # with few terms per output (small I, small K) a handful of flips can move an output past the
+    # end-to-end bound although every stage is right, so the bound is asserted at the sizes it is stated for
+    # and reported elsewhere.
+    if gate_end_to_end:
+        assert e_out <= TOL_FP8
     return cfg, g8, r
 
 
@@ -126,3 +137,22 @@ def test_fp8_qwen3_layer_32k_tokens():
     w = workloads.QWEN3_32K_FP8
     tokens = np.sort(np.random.default_rng(3).choice(w.T, size=128, replace=False))
     _fp8_case(w, tokens)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_fp8_random_small_shapes(seed):
+    """Seeded random shapes of the fp8 path (H, I multiples of 256; any T, E, K; with and without
+    the skewing router bias): every stage and every token against the quantising oracle, fused ==
+    staged."""
+    rng = np.random.default_rng(2000 + seed)
+    H, I = 256 * int(rng.integers(1, 3)), 256 * int(rng.integers(1, 3))
+    E = int(rng.integers(1, 25))
+    K = int(rng.integers(1, min(E, 8) + 1))
+    T = int(rng.integers(1, 900))
+    w = workloads.scaled(workloads.QWEN3_32K_FP8, name=f"fp8_rand{seed}_{T}_{H}_{E}_{K}_{I}", T=T, H=H, E=E, K=K, I=I,
+                         zipf_bias=bool(rng.integers(0, 2)))
+    cfg, g8, r = _fp8_case(w, None, gate_end_to_end=False)
+    out = moe.moe_prefill_layer(cfg, g8["x"], g8["w_router"], g8["bias"], g8["w_gate"], g8["w_up"], g8["w_down"],
+                                g8["s_gate"], g8["s_up"], g8["s_down"])
+    torch.cuda.synchronize()
+    assert torch.equal(out, r["out"])

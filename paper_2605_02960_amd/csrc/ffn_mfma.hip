@@ -35,9 +35,9 @@
 // epilogue's stores overlap the next tile's loads.
 //
 // Launch order.  Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b % 8).
-// Every XCD gets one contiguous range of the launch-order list (see tiles.hip), which walks an
-// expert's output in blocks of 8 x 4 tiles, so the 32 tiles in flight on an XCD share token rows
-// and weight rows in that XCD's L2.
+// The launch-order list (see tiles.hip) walks an expert's output in blocks of 8 x 4 tiles; it is
+// dealt to the XCDs in chunks of 32 entries, so the 32 tiles in flight on an XCD share token rows
+// and weight rows in that XCD's L2, and the 8 XCDs are on neighbouring blocks of the same expert.
 #include <type_traits>
 
 #include "common.h"
@@ -331,15 +331,16 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 3, wn = wave >> 2;
 
-    // ---- this workgroup's tiles: slots s, s + nslots, ... of its XCD's range of the launch order
+    // ---- this workgroup's tiles.  The launch-order list is cut into chunks of nslots entries
+    // (one per workgroup of an XCD); chunk c goes to XCD c % 8, so the 8 XCDs work on neighbouring
+    // stretches of the list (the same expert) at the same time and share it in the memory-side cache.
     const int total = a.table[0] * a.nct;
-    const int per_xcd = (total + 7) >> 3;
     const int xcd = blockIdx.x & 7;
     const int nslots = gridDim.x >> 3;
-    int slot = blockIdx.x >> 3;
-    const int l_end = min((xcd + 1) * per_xcd, total);
-    int L = xcd * per_xcd + slot;
-    if (slot >= per_xcd || L >= l_end) return;
+    const int slot = blockIdx.x >> 3;
+    const int l_end = total;
+    int L = xcd * nslots + slot;
+    if (L >= l_end) return;
 
     // ---- loader: thread handles chunk lc of rows lr + 64*i, i = 0..3, of both tiles
     const int lr = tid >> 3, lc = tid & 7;
@@ -468,9 +469,8 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // Invariant at the top of every K-step pair (kt even): LDS stage 0 holds step kt, register
     // set 1 holds (or is receiving) step kt+1, register set 0 is free.
     for (;;) {
-        slot += nslots;
-        L += nslots;
-        const bool has_next = slot < per_xcd && L < l_end;
+        L += 8 * nslots;
+        const bool has_next = L < l_end;
         if (has_next) load_ctx<MODE>(nxt, a, L, lr, lc);
         else nxt = cur;   // nothing follows: the two trailing loads re-read this tile (harmless)
         float* row_scale = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES) + (tile_parity << 8);

@@ -81,6 +81,13 @@ int32_t moe_sched_round(moe_sched_t *s, const moe_cost_model_t *cost, double thr
 int32_t moe_sched_blocks_stored(moe_sched_t *s, int32_t worker, const uint64_t *hashes, int64_t n);
 int32_t moe_sched_blocks_evicted(moe_sched_t *s, int32_t worker, const uint64_t *hashes, int64_t n);
 
+/* Progress report of an engine (App. B.3): `tokens` prompt tokens were executed on `worker`, so its
+ * counter decays by tokens * f_tok, never below zero: loads[worker] = max(0, loads[worker] -
+ * tokens * f_tok).  Enqueue (moe_sched_round with f_attn = 0) and decay use the same f_tok, which
+ * keeps the counter free of drift. */
+int32_t moe_sched_tokens_executed(const moe_sched_t *s, double *loads, int32_t worker, int64_t tokens,
+                                  double f_tok);
+
 /* Entries of one worker's table. */
 int32_t moe_sched_table_size(const moe_sched_t *s, int32_t worker, int64_t *committed,
                              int64_t *pending);

@@ -112,3 +112,10 @@ def schedule_round(tables, requests, threshold, f_tok, f_attn, loads=None):
             active.remove(i_star)
     return dict(assigned=assigned, matched=matched, delta=delta, loads=L,
                 saturated=[L[i] >= threshold for i in range(n)], last_delta=last_delta)
+
+
+def tokens_executed(loads, i, tokens, f_tok):
+    """App. B.3: the engine reports executed prompt tokens; L_i <- max(0, L_i - tokens * f_tok)."""
+    loads = list(loads)
+    loads[i] = max(0, loads[i] - tokens * f_tok)
+    return loads

@@ -15,5 +15,5 @@ from .binding import (  # noqa: F401
     moe_layer_weight_bytes, moe_prefill_layers_streamed, moe_layer_flops_per_token,
     moe_saturation_threshold_flops, moe_calibrated_threshold_flops,
     MoECostModel, moe_sched_create, moe_sched_destroy, moe_sched_hash_blocks, moe_sched_round,
-    moe_sched_blocks_stored, moe_sched_blocks_evicted, moe_sched_table_size,
+    moe_sched_blocks_stored, moe_sched_blocks_evicted, moe_sched_table_size, moe_sched_tokens_executed,
 )

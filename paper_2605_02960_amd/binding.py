@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
     "moe_sched_create", "moe_sched_destroy", "moe_sched_hash_blocks", "moe_sched_round",
     "moe_sched_blocks_stored", "moe_sched_blocks_evicted", "moe_sched_table_size",
+    "moe_sched_tokens_executed",
 )
 
 
@@ -113,6 +114,8 @@ def lib():
         L.moe_sched_blocks_stored.argtypes = [vp, i32, vp, i64]
         L.moe_sched_blocks_evicted.restype = i32
         L.moe_sched_blocks_evicted.argtypes = [vp, i32, vp, i64]
+        L.moe_sched_tokens_executed.restype = i32
+        L.moe_sched_tokens_executed.argtypes = [vp, vp, i32, i64, f64]
         L.moe_sched_table_size.restype = i32
         L.moe_sched_table_size.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         _lib = L
@@ -391,6 +394,14 @@ def moe_sched_blocks_stored(handle, worker, hashes):
 def moe_sched_blocks_evicted(handle, worker, hashes):
     h, hp = _np(hashes, np.uint64)
     _check(lib().moe_sched_blocks_evicted(handle, worker, hp, h.size), "moe_sched_blocks_evicted")
+
+
+def moe_sched_tokens_executed(handle, loads, worker, tokens, f_tok):
+    """loads (float64 numpy array) is updated in place."""
+    if not (isinstance(loads, np.ndarray) and loads.dtype == np.float64 and loads.flags.c_contiguous):
+        raise TypeError("loads must be a contiguous float64 numpy array (it is updated in place)")
+    _check(lib().moe_sched_tokens_executed(handle, ctypes.c_void_p(loads.ctypes.data), worker, tokens, float(f_tok)),
+           "moe_sched_tokens_executed")
 
 
 def moe_sched_table_size(handle, worker):

@@ -160,6 +160,16 @@ int32_t moe_sched_blocks_evicted(moe_sched_t* s, int32_t worker, const uint64_t*
     return MOE_OK;
 }
 
+int32_t moe_sched_tokens_executed(const moe_sched_t* s, double* loads, int32_t worker, int64_t tokens,
+                                  double f_tok) {
+    if (!s || !loads) return MOE_ERR_NULL_PTR;
+    if (!valid_worker(s, worker) || tokens < 0 || !(f_tok >= 0.0) || !std::isfinite(f_tok)) return MOE_ERR_BAD_SHAPE;
+    const double done = f_tok * static_cast<double>(tokens);
+    const double left = loads[worker] - done;
+    loads[worker] = left > 0.0 ? left : 0.0;
+    return MOE_OK;
+}
+
 int32_t moe_sched_table_size(const moe_sched_t* s, int32_t worker, int64_t* committed, int64_t* pending) {
     if (!s || !committed || !pending) return MOE_ERR_NULL_PTR;
     if (!valid_worker(s, worker)) return MOE_ERR_BAD_SHAPE;

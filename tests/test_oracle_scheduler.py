@@ -166,3 +166,22 @@ def test_hand_worked_trace():
     assert r["matched"] == g["expect"]["matched"]
     assert r["delta"] == g["expect"]["delta"]
     assert r["loads"] == g["expect"]["loads"]
+
+
+def test_counter_is_drift_free_with_one_constant():
+    """App. B.3: with f_attn = 0 a request adds u * f_tok at routing time and the engine's progress
+    reports take tokens * f_tok away again; once every uncached token has been executed the
+    counter is back at zero exactly, and it never goes below zero."""
+    f = 44_000
+    t = sch.BlockTables(2, 16)
+    prefix = list(range(100))
+    r = sch.schedule_round(t, [(prefix, 20), (prefix, 7), ([5] * 40, 3)], 10 ** 12, f, 0)
+    assert r["assigned"] == [0, 0, 1]
+    uncached = [100 + 20, (100 - 96) + 7, 40 + 3]            # the sibling re-uses 6 full blocks = 96 tokens
+    assert r["delta"] == [u * f for u in uncached]
+    loads = r["loads"]
+    loads = sch.tokens_executed(loads, 0, 64, f)
+    loads = sch.tokens_executed(loads, 0, uncached[0] + uncached[1] - 64, f)
+    loads = sch.tokens_executed(loads, 1, uncached[2], f)
+    assert loads == [0, 0]
+    assert sch.tokens_executed(loads, 1, 5, f) == [0, 0]

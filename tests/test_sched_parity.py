@@ -182,3 +182,31 @@ def test_argument_errors_change_nothing():
         assert loads.tolist() == [0.0, 0.0] and moe.moe_sched_table_size(h, 0) == (0, 0)
     finally:
         moe.moe_sched_destroy(h)
+
+
+def test_progress_reports_match_oracle():
+    f = 44_000
+    B = 16
+    reqs = workloads.generate_requests(50, 6, seed=11)
+    reqs_or = [(p.tolist(), s) for p, s in reqs]
+    tables = sch.BlockTables(4, B)
+    h = moe.moe_sched_create(4, B)
+    try:
+        loads = np.zeros(4)
+        assigned, matched, delta, n_done = _lib_round(h, reqs, B, 1e18, f, 0, loads)
+        r_or = sch.schedule_round(tables, reqs_or, 10 ** 18, f, 0)
+        _same((assigned, matched, delta, n_done), loads, r_or)
+        want = r_or["loads"]
+        rng = np.random.default_rng(0)
+        for _ in range(40):
+            i, tok = int(rng.integers(0, 4)), int(rng.integers(0, 3000))
+            moe.moe_sched_tokens_executed(h, loads, i, tok, f)
+            want = sch.tokens_executed(want, i, tok, f)
+            assert loads.tolist() == [float(v) for v in want]
+        assert min(loads) >= 0.0
+        with pytest.raises(moe.MoEError):
+            moe.moe_sched_tokens_executed(h, loads, 4, 1, f)
+        with pytest.raises(moe.MoEError):
+            moe.moe_sched_tokens_executed(h, loads, 0, -1, f)
+    finally:
+        moe.moe_sched_destroy(h)

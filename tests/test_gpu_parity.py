@@ -289,6 +289,9 @@ def test_full_size_layer_64k_tokens_zipf(w):
     tokens = np.unique(np.concatenate([rng.choice(w.T, size=2048, replace=False), rare[:64]]))
     _bf16_checks(w, d, g, cfg, r, info, tokens)
     assert torch.isfinite(out).all()
+    # the call as bench.py makes it (no taps: y stays in its compact form) gives the same bits
+    del taps, r
+    assert torch.equal(_fused(cfg, g), out)
 
 
 def test_bf16_layer_with_more_than_4gib_of_activations():
@@ -320,6 +323,9 @@ def test_bf16_layer_with_more_than_4gib_of_activations():
     tokens = np.unique(np.concatenate([rng.choice(w.T, size=160, replace=False), high]))
     _bf16_checks(w, d, g, cfg, r, info, tokens)
     assert torch.isfinite(out).all()
+    # the call as bench.py makes it (no taps: y stays in its compact form) gives the same bits
+    del taps, r
+    assert torch.equal(_fused(cfg, g), out)
 
 
 def test_y_block16_storage_is_the_quantiser_applied_to_the_float32_result():

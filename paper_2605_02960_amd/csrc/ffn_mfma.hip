@@ -602,16 +602,18 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     if (st != MOE_OK) return st;
 
     // one persistent workgroup per compute unit (the 128 KB of LDS allow no second one)
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
+    // (compute-unit count and the kernels' LDS attribute are looked up once per device)
+    static int n_cu_of_device[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_ERR_LAUNCH_FAILED;
+    if (n_cu_of_device[dev] == 0) {
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return MOE_ERR_LAUNCH_FAILED;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return MOE_ERR_LAUNCH_FAILED;
         if (set_kernel_attributes<false>() != MOE_OK || set_kernel_attributes<true>() != MOE_OK)
             return MOE_ERR_LAUNCH_FAILED;
-        n_cu = prop.multiProcessorCount;
+        n_cu_of_device[dev] = prop.multiProcessorCount;
     }
+    const int n_cu = n_cu_of_device[dev];
     const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
 
     // fp8: quantise the x rows once per token, and carry each sorted row's scale along

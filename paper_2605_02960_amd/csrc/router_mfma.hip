@@ -155,12 +155,14 @@ int32_t launch_router_logits_mfma(const moe_config_t& c, const void* x, const fl
     if (c.T == 0) return MOE_OK;
     if ((uint64_t)c.T * c.H * 2 > 0xFFFFFFFFull || (uint64_t)3 * c.E * c.H * 2 > 0xFFFFFFFFull)
         return MOE_ERR_UNSUPPORTED;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static bool attr_done[64] = {};   // per device
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_ERR_LAUNCH_FAILED;
+    if (!attr_done[dev]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&router_mfma_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R_STAGE) != hipSuccess)
             return MOE_ERR_LAUNCH_FAILED;
-        attr_done = true;
+        attr_done[dev] = true;
     }
     uint16_t* w3 = static_cast<uint16_t*>(ws);
     const size_t n = (size_t)c.E * c.H;

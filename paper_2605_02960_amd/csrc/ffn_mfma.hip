@@ -128,8 +128,8 @@ __device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, i
         t.a_off[i] = src * a.lda_bytes + lc * 16;
     }
 }
-// MFMA block edge: bf16 uses v_mfma_f32_16x16x32_bf16 (less accumulator traffic per flop than
-// 32x32x16, measured ~5-8 % faster in this pipeline), fp8 uses v_mfma_f32_32x32x64_f8f6f4.
+// MFMA block edge: 32 (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x64_f8f6f4).  16 selects
+// v_mfma_f32_16x16x32_bf16 for the bf16 path: faster in a bare MFMA loop, slower in this kernel.
 #ifndef MOE_BF16_BLK
 #define MOE_BF16_BLK 32
 #endif

@@ -174,6 +174,12 @@ def main():
                 acc[n].append(ev.elapsed_ms(*ps[k]))
                 moe.moe_set_profile_events(k, None, None)
         res["kernel_ms"] = {n: round(float(np.mean(v)), 4) for n, v in acc.items()}
+        # the HBM-bound step: algorithmic bytes of the combine (y once, in the form the fused call
+        # keeps it in, positions and weights, the output once) over its time
+        y_bytes = rows * (w.H * 4 if w.dtype == "fp32" else w.H * 2 + w.H // 16)
+        comb_bytes = y_bytes + rows * 8 + w.T * w.H * 4
+        res["combine_TBps"] = round(comb_bytes / (res["kernel_ms"]["combine"] * 1e-3) / 1e12, 2)
+        res["ffn_tflops"] = round(flops_ffn / ((res["kernel_ms"]["gate_up"] + res["kernel_ms"]["down"]) * 1e-3) / 1e12, 1)
 
     if not a.no_cpu_baseline:
         from oracle import moe_oracle as mo

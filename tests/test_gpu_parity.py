@@ -378,3 +378,32 @@ def test_bf16_random_small_shapes(seed):
     cfg32 = gu.config_for(w, flags=moe.FLAG_Y_F32)
     o32 = _fused(cfg32, g)
     assert gu.max_err_over_rms(r["out"].cpu().numpy(), o32.cpu().numpy()) <= 5e-4
+
+
+def test_fused_call_can_be_captured_in_a_graph():
+    """The library enqueues kernels only (no allocation, no host synchronisation, no memset node),
+    so a caller may capture the fused call in a HIP graph: three replays, with eager work on the
+    same buffers in between, each equal to the eager result bit for bit."""
+    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name="bf16_graph", T=1000, H=256, E=24, K=4, I=384)
+    d = workloads.generate(w)
+    g = gu.upload(d)
+    cfg = gu.config_for(w)
+    ws = torch.empty(moe.moe_workspace_bytes(cfg, moe.CALL_PREFILL_LAYER), dtype=torch.uint8, device=gu.DEV)
+    args = (cfg, g["x"], g["w_router"], g["bias"], g["w_gate"], g["w_up"], g["w_down"])
+    want = moe.moe_prefill_layer(*args, ws=ws).clone()         # also the first call: kernel attributes are set here
+    torch.cuda.synchronize()
+    out = torch.empty_like(want)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        moe.moe_prefill_layer(*args, out=out, ws=ws)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)                                      # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), rep
+        eager = moe.moe_prefill_layer(*args, ws=ws)             # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(eager, want)

@@ -103,10 +103,32 @@ struct TileCtx {
     int e;
 };
 
+#ifndef MOE_DMA
+#define MOE_DMA 1
+#endif
+// How the two operand tiles of a K step get into LDS.
+//   DMA (default): global_load_lds_dwordx4 writes 16 bytes per lane straight into LDS, lane l of
+//   an instruction at LDS position base + 16*l; one instruction covers 8 tile rows (8 chunks of 16
+//   bytes each), wave w issues the 4 instructions of rows 32w .. 32w+31 of both tiles.  The row
+//   swizzle is applied on the global side: the lane that fills position c' of row r fetches chunk
+//   c' ^ ((r >> 1) & 7).  No staging registers, no LDS store instructions.
+//   Register-staged: thread t loads chunk t % 8 of rows t / 8 + 64 i into registers and stores
+//   them to LDS (swizzled) one K step later.
+constexpr bool LOADER_DMA = MOE_DMA != 0;
+__device__ __forceinline__ void loader_pos(int tid, int i, int& row, int& chunk) {
+    if (LOADER_DMA) {
+        row = (tid >> 6) * 32 + i * 8 + ((tid & 63) >> 3);
+        chunk = (tid & 7) ^ ((row >> 1) & 7);
+    } else {
+        row = (tid >> 3) + 64 * i;
+        chunk = tid & 7;
+    }
+}
+
 // Everything of a tile except the weight-row offsets (which are cheap to recompute and are only
 // filled in when the tile is about to be loaded, to keep registers free during the K loop).
 template <int MODE>
-__device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, int lr, int lc) {
+__device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, int tid) {
     constexpr int NCOLS = (MODE == MODE_GATE_UP) ? 128 : 256;
     const int packed = a.order[L];
     const int rt = packed >> 8, ct = packed & 255;
@@ -123,9 +145,11 @@ __device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, i
     // however many routed rows there are.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int r = min(t.row0 + lr + 64 * i, t.row_end - 1);      // rows past the group's end re-read its last row
+        int lrow, lchunk;
+        loader_pos(tid, i, lrow, lchunk);
+        int r = min(t.row0 + lrow, t.row_end - 1);             // rows past the group's end re-read its last row
         const uint32_t src = (MODE == MODE_GATE_UP) ? (uint32_t)(a.perm[r] / a.kdiv) : (uint32_t)(r - t.row0);
-        t.a_off[i] = src * a.lda_bytes + lc * 16;
+        t.a_off[i] = src * a.lda_bytes + lchunk * 16;
     }
 }
 // MFMA block edge: 32 (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x64_f8f6f4).  16 selects
@@ -157,12 +181,14 @@ __device__ __forceinline__ int weight_col_of_lds_row(int R) {
     return (R & 128) + (nj >> 2) * (4 * BE) + 4 * (w % BE) + (nj & 3);
 }
 template <int MODE, int BE>
-__device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int lr, int lc) {
+__device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int tid) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int wr = t.n0 + weight_col_of_lds_row<MODE, BE>(lr + 64 * i);
+        int lrow, lchunk;
+        loader_pos(tid, i, lrow, lchunk);
+        int wr = t.n0 + weight_col_of_lds_row<MODE, BE>(lrow);
         wr = min(wr, a.N - 1);
-        t.b_off[i] = (uint32_t)wr * a.ldb_bytes + lc * 16;
+        t.b_off[i] = (uint32_t)wr * a.ldb_bytes + lchunk * 16;
     }
 }
 
@@ -323,6 +349,23 @@ __device__ __forceinline__ i32x8 load_frag8(const char* row, uint32_t off0, uint
     return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
 }
 
+// A pointer that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// 16 bytes per lane from global memory (scalar base + 32-bit lane offset) straight into LDS at
+// m0 + 16 * lane.  Completion is tracked by vmcnt like any other vector memory load.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const char* base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+
 template <int MODE, bool FP8>
 __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -456,23 +499,102 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         }                                                                                  \
     }
 
+    // ---- direct-to-LDS loader: wave w fills rows 32w .. 32w+31 of both operand tiles, 8 rows per
+    // instruction; the K offset is added to the lane offsets, the bases are scalar
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    const uint32_t dma_row0 = (uint32_t)(wave_u * 32) * ROW_BYTES;
+#define MOE_DMA_ISSUE(STAGE_, CTX_, KT_)                                                  \
+    {                                                                                     \
+        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                  \
+        const char* abase = uniform_ptr(                                                  \
+            (MODE == MODE_GATE_UP) ? a.A : a.A + (size_t)CTX_.row0 * a.lda_bytes);        \
+        const char* bbase =                                                               \
+            uniform_ptr((MODE == MODE_DOWN || wave_u < 4) ? CTX_.b0e : CTX_.b1e);         \
+        const uint32_t st = __builtin_amdgcn_readfirstlane(                               \
+            lds_base + (STAGE_) * STAGE_BYTES + dma_row0);                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                     \
+            dma16(st + i * 8 * ROW_BYTES, CTX_.a_off[i] + kb, abase);                     \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                     \
+            dma16(st + TILE_BYTES + i * 8 * ROW_BYTES, CTX_.b_off[i] + kb, bbase);        \
+    }
+    // issue order with the direct-to-LDS loader: the loads come first (program order), then the
+    // fragments of the first K slice, then every MFMA followed by one fragment read of the next slice
+#define MOE_ISSUE_ORDER_DMA()                                                              \
+    if constexpr (BE == 32) {                                                              \
+        constexpr int NMF = NM * NN, NKK = FP8 ? 2 : 4, RPF = FP8 ? 2 : 1;                 \
+        constexpr int NRS = NM + NN;                                                       \
+        MOE_SGB(0x100, NRS * RPF);                                                         \
+        _Pragma("unroll") for (int kk = 0; kk < NKK; ++kk) {                               \
+            _Pragma("unroll") for (int j = 0; j < NMF; ++j) {                              \
+                MOE_SGB(0x008, 1);                                                         \
+                if (kk < NKK - 1 && j < NRS) MOE_SGB(0x100, RPF);                          \
+            }                                                                              \
+        }                                                                                  \
+    }
+    // bf16: the fragments of K slice k+1 are read (into the other of two fragment sets) before
+    // the MFMAs of slice k are issued; the staging registers that the direct-to-LDS loader no
+    // longer needs pay for the second set
+    bf16x8 fa0[NM], fb0[NN], fa1[NM], fb1[NN];
+#define MOE_FREAD(BUF_, STAGE_, KK_)                                                       \
+    {                                                                                      \
+        const char* st = smem + (STAGE_) * STAGE_BYTES;                                    \
+        _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) fa##BUF_[mi] =                   \
+            *reinterpret_cast<const bf16x8*>(st + xa_row + mi * BE * ROW_BYTES + frag_off[KK_]); \
+        _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) fb##BUF_[nj] =                   \
+            *reinterpret_cast<const bf16x8*>(st + wb_base + wb_off(nj) + frag_off[KK_]);   \
+    }
+#define MOE_FMFMA(BUF_)                                                                    \
+    {                                                                                      \
+        _Pragma("unroll") for (int nj = 0; nj < NN; ++nj)                                  \
+            _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                              \
+                acc[nj][mi] = mfma_bf16(fa##BUF_[mi], fb##BUF_[nj], acc[nj][mi]);          \
+    }
+#define MOE_COMPUTE_DMA(STAGE_)                                                            \
+    if constexpr (!FP8 && BE == 32) {                                                      \
+        MOE_FREAD(0, STAGE_, 0);                                                           \
+        MOE_FREAD(1, STAGE_, 1);                                                           \
+        MOE_FMFMA(0);                                                                      \
+        MOE_FREAD(0, STAGE_, 2);                                                           \
+        MOE_FMFMA(1);                                                                      \
+        MOE_FREAD(1, STAGE_, 3);                                                           \
+        MOE_FMFMA(0);                                                                      \
+        MOE_FMFMA(1);                                                                      \
+    } else {                                                                               \
+        MOE_COMPUTE(STAGE_);                                                               \
+    }
+    // one K step: multiply LDS stage S_ while step KT_ of CTX_ lands in the other stage
+#define MOE_STEP_DMA(S_, CTX_, KT_)                                                        \
+    {                                                                                      \
+        MOE_DMA_ISSUE(1 - (S_), CTX_, KT_);                                                \
+        MOE_COMPUTE_DMA(S_);                                                               \
+        MOE_ISSUE_ORDER_DMA();                                                             \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                   \
+        __syncthreads();                                                                   \
+    }
+
     const int KT = a.KT;   // even, >= 2
     TileCtx cur, nxt;
-    load_ctx<MODE>(cur, a, L, lr, lc);
-    fill_b_off<MODE, BE>(cur, a, lr, lc);
-    MOE_GLOAD(0, cur, 0);
-    MOE_GLOAD(1, cur, 1);
-    MOE_LSTORE(0, 0);
+    load_ctx<MODE>(cur, a, L, tid);
+    fill_b_off<MODE, BE>(cur, a, tid);
+    if constexpr (LOADER_DMA) {
+        MOE_DMA_ISSUE(0, cur, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        MOE_GLOAD(0, cur, 0);
+        MOE_GLOAD(1, cur, 1);
+        MOE_LSTORE(0, 0);
+    }
     __syncthreads();
 
     int tile_parity = 0;
-    // Invariant at the top of every K-step pair (kt even): LDS stage 0 holds step kt, register
-    // set 1 holds (or is receiving) step kt+1, register set 0 is free.
+    // Invariant at the top of every K-step pair (kt even): LDS stage 0 holds step kt.  Register-
+    // staged loader: register set 1 holds (or is receiving) step kt+1, register set 0 is free.
     for (;;) {
         L += 8 * nslots;
         const bool has_next = L < l_end;
-        if (has_next) load_ctx<MODE>(nxt, a, L, lr, lc);
-        else nxt = cur;   // nothing follows: the two trailing loads re-read this tile (harmless)
+        if (has_next) load_ctx<MODE>(nxt, a, L, tid);
+        else nxt = cur;   // nothing follows: the trailing loads re-read this tile (harmless)
         float* row_scale = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES) + (tile_parity << 8);
         if (FP8 && tid < BM) row_scale[tid] = a.sA[min(cur.row0 + tid, cur.row_end - 1)];
         tile_parity ^= 1;   // the buffer is read in this tile's epilogue, many barriers from here
@@ -484,30 +606,41 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #pragma unroll
                 for (int v = 0; v < Blk<FP8>::VLEN; ++v) acc[nj][mi][v] = 0.f;
 
-        for (int kt = 0; kt < KT - 2; kt += 2) {
-            MOE_GLOAD(0, cur, kt + 2);
+        if constexpr (LOADER_DMA) {
+            for (int kt = 0; kt < KT - 2; kt += 2) {
+                MOE_STEP_DMA(0, cur, kt + 1);
+                MOE_STEP_DMA(1, cur, kt + 2);
+            }
+            // last pair of this tile: the second load is step 0 of the next tile
+            MOE_STEP_DMA(0, cur, KT - 1);
+            fill_b_off<MODE, BE>(nxt, a, tid);
+            MOE_STEP_DMA(1, nxt, 0);
+        } else {
+            for (int kt = 0; kt < KT - 2; kt += 2) {
+                MOE_GLOAD(0, cur, kt + 2);
+                MOE_COMPUTE(0);
+                MOE_LSTORE(1, 1);
+                MOE_ISSUE_ORDER();
+                __syncthreads();
+                MOE_GLOAD(1, cur, kt + 3);
+                MOE_COMPUTE(1);
+                MOE_LSTORE(0, 0);
+                MOE_ISSUE_ORDER();
+                __syncthreads();
+            }
+            // last pair of this tile: its two loads are steps 0 and 1 of the next tile
+            fill_b_off<MODE, BE>(nxt, a, tid);
+            MOE_GLOAD(0, nxt, 0);
             MOE_COMPUTE(0);
             MOE_LSTORE(1, 1);
             MOE_ISSUE_ORDER();
             __syncthreads();
-            MOE_GLOAD(1, cur, kt + 3);
+            MOE_GLOAD(1, nxt, 1);
             MOE_COMPUTE(1);
             MOE_LSTORE(0, 0);
             MOE_ISSUE_ORDER();
             __syncthreads();
         }
-        // last pair of this tile: its two loads are steps 0 and 1 of the next tile
-        fill_b_off<MODE, BE>(nxt, a, lr, lc);
-        MOE_GLOAD(0, nxt, 0);
-        MOE_COMPUTE(0);
-        MOE_LSTORE(1, 1);
-        MOE_ISSUE_ORDER();
-        __syncthreads();
-        MOE_GLOAD(1, nxt, 1);
-        MOE_COMPUTE(1);
-        MOE_LSTORE(0, 0);
-        MOE_ISSUE_ORDER();
-        __syncthreads();
 
         store_tile<MODE, FP8, acc_t>(acc, a, cur, wm, wn, fr, fq, row_scale);
         if (!has_next) break;
@@ -518,6 +651,12 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_COMPUTE
 #undef MOE_LOAD_FRAG8
 #undef MOE_ISSUE_ORDER
+#undef MOE_ISSUE_ORDER_DMA
+#undef MOE_DMA_ISSUE
+#undef MOE_STEP_DMA
+#undef MOE_COMPUTE_DMA
+#undef MOE_FREAD
+#undef MOE_FMFMA
 #undef MOE_SGB
 }
 

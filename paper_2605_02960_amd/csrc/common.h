@@ -87,12 +87,13 @@ inline size_t tile_table_bytes(const moe_config_t& c, int bm) {
 // first_out (optional, [E+1]): index of every expert's first row tile.
 int32_t launch_build_tile_table(const moe_config_t& c, const int32_t* offsets, int bm,
                                 int32_t* table, int32_t* first_out, hipStream_t s);
-// order[L] = rt << 8 | ct for launch slot L (nct column tiles per row tile, nct <= 256).
+// order[L] = (expert, first sorted row, end row, column tile) of launch slot L (nct column tiles
+// per row tile): everything a workgroup needs to start a tile, in one 16-byte load.
 inline size_t tile_order_bytes(const moe_config_t& c, int bm, int nct) {
-    return align_up(sizeof(int32_t) * (size_t)max_row_tiles(c, bm) * nct, 256);
+    return align_up(sizeof(int4) * (size_t)max_row_tiles(c, bm) * nct, 256);
 }
-int32_t launch_build_tile_order(const moe_config_t& c, const int32_t* first, int nct, int gr, int gc,
-                                int32_t* order, hipStream_t s);
+int32_t launch_build_tile_order(const moe_config_t& c, const int32_t* first, const int32_t* offsets, int bm,
+                                int nct, int gr, int gc, int4* order, hipStream_t s);
 
 // ---- ffn_f32.hip
 size_t ffn_f32_ws_bytes(const moe_config_t& c);

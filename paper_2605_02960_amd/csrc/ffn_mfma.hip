@@ -19,20 +19,25 @@
 // of code products and the scales are applied in the epilogue.
 //
 // LDS.  A tile is [256 rows][128 bytes] in 8 chunks of 16 bytes per row; chunk c of
-// row r sits at position c ^ ((r >> 1) & 7), which makes both the 16-byte stores of the loader
-// and the 16-byte fragment reads of the MFMA operands free of bank conflicts.  Two stages
-// (2 x 64 KB) are double-buffered with one barrier per K step.
+// row r sits at position c ^ ((r >> 1) & 7), which makes the 16-byte fragment reads of the MFMA
+// operands free of bank conflicts.  Two stages (2 x 64 KB) are double-buffered with one barrier
+// per K step.
 //
-// Issue order.  Inside a K step every MFMA is followed by at most one LDS fragment read, global
-// load or LDS store (scheduling group barriers), so that the matrix pipe is fed while the memory
-// operations of the next K slice and of the K steps ahead are issued in its shadow.
+// Loader.  The operand tiles go from global memory straight into LDS (global_load_lds_dwordx4:
+// 16 bytes per lane, full 128-byte lines per row, no staging registers and no LDS store
+// instructions).  The instruction writes lane l at LDS base + 16 l, so the swizzle is applied on
+// the global side (the lane that fills position c' of row r fetches chunk c' ^ ((r >> 1) & 7)).
+// Rows of x are gathered through the lane offsets.  The tile for K step k+1 is requested at the
+// top of step k and awaited (vmcnt(0) + barrier) at its end.  A register-staged loader (global
+// load to registers, LDS store one K step later, prefetch distance 2) is kept behind MOE_DMA=0.
 //
-// Pipeline.  Global loads are full 128-byte lines per row (one K step of one row), staged in two
-// register sets: the tile for K step k+2 is requested while step k is multiplied, so every request
-// has two K steps of MFMA work to hide behind.  The kernel is persistent (one workgroup per CU):
-// the loads that a tile's last two K steps would issue are the first two K steps of the
-// workgroup's NEXT tile, so consecutive tiles chain without draining the pipeline and the
-// epilogue's stores overlap the next tile's loads.
+// Issue order.  bf16: the fragments of K slice s+1 are read into the second of two fragment
+// register sets before the MFMAs of slice s are issued, and scheduling group barriers put one
+// fragment read behind each MFMA, so the matrix pipe never waits for LDS.  fp8 keeps one set.
+//
+// Pipeline.  The kernel is persistent (one workgroup per CU): the load that a tile's last K step
+// issues is the first K step of the workgroup's NEXT tile, so consecutive tiles chain without
+// draining the pipeline and the epilogue's stores overlap the next tile's loads.
 //
 // Launch order.  Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b % 8).
 // The launch-order list (see tiles.hip) walks an expert's output in blocks of 8 x 4 tiles; it is
@@ -82,8 +87,7 @@ struct MfmaArgs {
     const float* sB0;       // fp8: per-output-channel scales [E][N] of B0
     const float* sB1;       // fp8: same for B1
     const int32_t* table;   // row tiles: [0] = count, then (expert, first row) pairs
-    const int32_t* order;   // launch slot -> rt << 8 | ct
-    const int32_t* offsets;
+    const int4* order;      // launch slot -> (expert, first row, end row, column tile)
     char* C;                // act [P,I] bf16, or y [P,H]: float32 (y_mode 0, 1) or int16 codes (y_mode 2)
     uint8_t* Cs;            // y_mode 2: block exponents [P][N/16]
     int32_t y_mode;         // down only, see Y_* below
@@ -103,52 +107,61 @@ struct TileCtx {
     int e;
 };
 
-#ifndef MOE_DMA
-#define MOE_DMA 1
-#endif
-// How the two operand tiles of a K step get into LDS.
-//   DMA (default): global_load_lds_dwordx4 writes 16 bytes per lane straight into LDS, lane l of
-//   an instruction at LDS position base + 16*l; one instruction covers 8 tile rows (8 chunks of 16
-//   bytes each), wave w issues the 4 instructions of rows 32w .. 32w+31 of both tiles.  The row
-//   swizzle is applied on the global side: the lane that fills position c' of row r fetches chunk
-//   c' ^ ((r >> 1) & 7).  No staging registers, no LDS store instructions.
-//   Register-staged: thread t loads chunk t % 8 of rows t / 8 + 64 i into registers and stores
-//   them to LDS (swizzled) one K step later.
-constexpr bool LOADER_DMA = MOE_DMA != 0;
+// How the two operand tiles of a K step get into LDS: global_load_lds_dwordx4 writes 16 bytes per
+// lane straight into LDS, lane l of an instruction at LDS position base + 16*l; one instruction
+// covers 8 tile rows (8 chunks of 16 bytes each), wave w issues the 4 instructions of rows
+// 32w .. 32w+31 of both tiles.  The row swizzle is applied on the global side: the lane that fills
+// position c' of row r fetches chunk c' ^ ((r >> 1) & 7).
 __device__ __forceinline__ void loader_pos(int tid, int i, int& row, int& chunk) {
-    if (LOADER_DMA) {
-        row = (tid >> 6) * 32 + i * 8 + ((tid & 63) >> 3);
-        chunk = (tid & 7) ^ ((row >> 1) & 7);
-    } else {
-        row = (tid >> 3) + 64 * i;
-        chunk = tid & 7;
-    }
+    row = (tid >> 6) * 32 + i * 8 + ((tid & 63) >> 3);
+    chunk = (tid & 7) ^ ((row >> 1) & 7);
 }
 
-// Everything of a tile except the weight-row offsets (which are cheap to recompute and are only
-// filled in when the tile is about to be loaded, to keep registers free during the K loop).
+// A record that is the same in every lane, moved to scalar registers.  Volatile, so that it stays
+// where it is written (behind a K step's wait for memory) instead of moving up into the MFMA
+// stream, where the wait for its load would stall the matrix pipe.  The trailing s_nop covers the
+// wait states between a vector instruction's scalar result and any kind of reader.
+__device__ __forceinline__ int4 uniform_rec(const int4 r) {
+    int4 o;
+    asm volatile("v_readfirstlane_b32 %0, %4\n\tv_readfirstlane_b32 %1, %5\n\t"
+                 "v_readfirstlane_b32 %2, %6\n\tv_readfirstlane_b32 %3, %7\n\ts_nop 4"
+                 : "=s"(o.x), "=s"(o.y), "=s"(o.z), "=s"(o.w)
+                 : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    return o;
+}
+// A tile's context from its launch-order record (expert, first row, end row, column tile).  For
+// gate/up this issues the loads of the tile's perm entries; their values (and for down the row
+// numbers) stay in a_off as they are until fill_a_off turns them into byte offsets, so that no
+// wait for them stands between two tiles.
 template <int MODE>
-__device__ __forceinline__ void load_ctx(TileCtx& t, const MfmaArgs& a, int L, int tid) {
+__device__ __forceinline__ void ctx_from_rec(TileCtx& t, const MfmaArgs& a, const int4 rec, int tid) {
     constexpr int NCOLS = (MODE == MODE_GATE_UP) ? 128 : 256;
-    const int packed = a.order[L];
-    const int rt = packed >> 8, ct = packed & 255;
-    const int e = a.table[1 + 2 * rt];
+    const int e = rec.x;
     t.e = e;
-    t.row0 = a.table[2 + 2 * rt];
-    t.row_end = min(a.offsets[e + 1], t.row0 + BM);
-    t.n0 = ct * NCOLS;
+    t.row0 = rec.y;
+    t.row_end = rec.z;
+    t.n0 = rec.w * NCOLS;
     const size_t wbytes = (size_t)a.N * a.ldb_bytes;
     t.b0e = a.B0 + (size_t)e * wbytes;
     t.b1e = (MODE == MODE_GATE_UP) ? a.B1 + (size_t)e * wbytes : t.b0e;
-    // gate/up gathers rows of x (offsets from x itself, T*H*esz < 4 GiB); down reads the tile's own
-    // contiguous rows of act, so its offsets are taken from the tile's first row and stay small
-    // however many routed rows there are.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int lrow, lchunk;
         loader_pos(tid, i, lrow, lchunk);
-        int r = min(t.row0 + lrow, t.row_end - 1);             // rows past the group's end re-read its last row
-        const uint32_t src = (MODE == MODE_GATE_UP) ? (uint32_t)(a.perm[r] / a.kdiv) : (uint32_t)(r - t.row0);
+        const int r = min(t.row0 + lrow, t.row_end - 1);       // rows past the group's end re-read its last row
+        t.a_off[i] = (MODE == MODE_GATE_UP) ? (uint32_t)a.perm[r] : (uint32_t)(r - t.row0);
+    }
+}
+// gate/up gathers rows of x (offsets from x itself, T*H*esz < 4 GiB); down reads the tile's own
+// contiguous rows of act, so its offsets are taken from the tile's first row and stay small
+// however many routed rows there are.
+template <int MODE>
+__device__ __forceinline__ void fill_a_off(TileCtx& t, const MfmaArgs& a, int tid) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int lrow, lchunk;
+        loader_pos(tid, i, lrow, lchunk);
+        const uint32_t src = (MODE == MODE_GATE_UP) ? t.a_off[i] / (uint32_t)a.kdiv : t.a_off[i];
         t.a_off[i] = src * a.lda_bytes + lchunk * 16;
     }
 }
@@ -385,10 +398,6 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     int L = xcd * nslots + slot;
     if (L >= l_end) return;
 
-    // ---- loader: thread handles chunk lc of rows lr + 64*i, i = 0..3, of both tiles
-    const int lr = tid >> 3, lc = tid & 7;
-    const uint32_t st_off = lr * ROW_BYTES + ((lc ^ ((lr >> 1) & 7)) << 4);
-
     // ---- fragment read offsets.  Lane = (fq, fr): fr = row of the MFMA block, fq = which 16-byte
     // (bf16) or 32-byte (fp8) piece of the block's K slice the lane supplies.
     constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN;
@@ -413,27 +422,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 
     typedef typename std::conditional<BE == 32, f32x16, f32x4>::type acc_t;
     acc_t acc[NN][NM];
-    u32x4 ra0[4], rb0[4], ra1[4], rb1[4];   // the two register sets of staged global loads
 
-#define MOE_GLOAD(SET_, CTX_, KT_)                                                        \
-    {                                                                                     \
-        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                  \
-        const char* abase =                                                               \
-            (MODE == MODE_GATE_UP) ? a.A : a.A + (size_t)CTX_.row0 * a.lda_bytes;         \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                   \
-            ra##SET_[i] = *reinterpret_cast<const u32x4*>(abase + (CTX_.a_off[i] + kb));  \
-            rb##SET_[i] = *reinterpret_cast<const u32x4*>(                                \
-                ((i < 2 || MODE == MODE_DOWN) ? CTX_.b0e : CTX_.b1e) + (CTX_.b_off[i] + kb)); \
-        }                                                                                 \
-    }
-#define MOE_LSTORE(SET_, STAGE_)                                                          \
-    {                                                                                     \
-        char* base = smem + (STAGE_) * STAGE_BYTES + st_off;                              \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                   \
-            *reinterpret_cast<u32x4*>(base + i * 64 * ROW_BYTES) = ra##SET_[i];           \
-            *reinterpret_cast<u32x4*>(base + TILE_BYTES + i * 64 * ROW_BYTES) = rb##SET_[i]; \
-        }                                                                                 \
-    }
 #define MOE_LOAD_FRAG8(PTR_, KK_) load_frag8((PTR_), frag_off[(KK_) * 2], frag_off[(KK_) * 2 + 1])
 #define MOE_COMPUTE(STAGE_)                                                               \
     {                                                                                     \
@@ -466,38 +455,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         }                                                                                 \
     }
 
-    // Issue order inside one K step, imposed on the compiler's scheduler: the fragments of the first
-    // K slice, then every MFMA followed by at most one other memory operation, so that the LDS
-    // reads of the next slice, the LDS stores of the other stage and the global loads two steps
-    // ahead all issue in the shadow of the matrix pipe instead of in a block of their own before
-    // the barrier.  Per slice: MFMA j is followed by the next slice's fragment reads for j < NRS,
-    // by a global load for L0 <= j < L0 + NOTH and by an LDS store for W0 <= j < W0 + NOTH.
-    // Which placement the scheduler can honour, and what it gains, differs by kernel (measured:
-    // gate/up +12 %, down +8 %, fp8 gate/up +4 %, fp8 down -3 % and therefore left alone).
-#ifndef MOE_ISSUE_ORDER_MODE
-#define MOE_ISSUE_ORDER_MODE -1   // -1: per-kernel choice below, 0: off, 1: loads and stores early, 2: late
-#endif
-    constexpr int ISSUE_ORDER = MOE_ISSUE_ORDER_MODE >= 0 ? MOE_ISSUE_ORDER_MODE
-                              : (BE != 32)                ? 0
-                              : (MODE == MODE_GATE_UP)    ? 1
-                              : (FP8 ? 0 : 2);
 #define MOE_SGB(MASK_, N_) __builtin_amdgcn_sched_group_barrier(MASK_, N_, 0)
-#define MOE_ISSUE_ORDER()                                                                  \
-    if constexpr (ISSUE_ORDER != 0) {                                                      \
-        constexpr int NMF = NM * NN, NKK = FP8 ? 2 : 4, RPF = FP8 ? 2 : 1;                 \
-        constexpr int NRS = NM + NN, NOTH = 8 / NKK;                                       \
-        constexpr int L0 = ISSUE_ORDER == 1 ? 0 : NMF - 2 * NOTH;                          \
-        constexpr int W0 = ISSUE_ORDER == 1 ? NOTH : NMF - NOTH;                           \
-        MOE_SGB(0x100, NRS * RPF);                          /* LDS reads of slice 0 */     \
-        _Pragma("unroll") for (int kk = 0; kk < NKK; ++kk) {                               \
-            _Pragma("unroll") for (int j = 0; j < NMF; ++j) {                              \
-                MOE_SGB(0x008, 1);                          /* one MFMA */                 \
-                if (kk < NKK - 1 && j < NRS) MOE_SGB(0x100, RPF);                          \
-                if (j >= L0 && j < L0 + NOTH) MOE_SGB(0x020, 1);   /* global load */       \
-                if (j >= W0 && j < W0 + NOTH) MOE_SGB(0x200, 1);   /* LDS store */         \
-            }                                                                              \
-        }                                                                                  \
-    }
 
     // ---- direct-to-LDS loader: wave w fills rows 32w .. 32w+31 of both operand tiles, 8 rows per
     // instruction; the K offset is added to the lane offsets, the bases are scalar
@@ -518,9 +476,10 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                     \
             dma16(st + TILE_BYTES + i * 8 * ROW_BYTES, CTX_.b_off[i] + kb, bbase);        \
     }
-    // issue order with the direct-to-LDS loader: the loads come first (program order), then the
+    // Issue order inside one K step, imposed on the compiler's scheduler (which otherwise gathers
+    // the LDS reads in blocks of their own): the loads come first (program order), then the
     // fragments of the first K slice, then every MFMA followed by one fragment read of the next slice
-#define MOE_ISSUE_ORDER_DMA()                                                              \
+#define MOE_ISSUE_ORDER()                                                              \
     if constexpr (BE == 32) {                                                              \
         constexpr int NMF = NM * NN, NKK = FP8 ? 2 : 4, RPF = FP8 ? 2 : 1;                 \
         constexpr int NRS = NM + NN;                                                       \
@@ -550,113 +509,95 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                              \
                 acc[nj][mi] = mfma_bf16(fa##BUF_[mi], fb##BUF_[nj], acc[nj][mi]);          \
     }
-#define MOE_COMPUTE_DMA(STAGE_)                                                            \
+    // first K slice of a tile: the accumulator input is the constant zero
+#define MOE_FMFMA_Z(BUF_)                                                                  \
+    {                                                                                      \
+        _Pragma("unroll") for (int nj = 0; nj < NN; ++nj)                                  \
+            _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                              \
+                acc[nj][mi] = mfma_bf16(fa##BUF_[mi], fb##BUF_[nj], acc_t{});              \
+    }
+#define MOE_COMPUTE_STEP(STAGE_, FIRST_)                                                   \
     if constexpr (!FP8 && BE == 32) {                                                      \
         MOE_FREAD(0, STAGE_, 0);                                                           \
         MOE_FREAD(1, STAGE_, 1);                                                           \
-        MOE_FMFMA(0);                                                                      \
+        if constexpr (FIRST_) MOE_FMFMA_Z(0) else MOE_FMFMA(0);                            \
         MOE_FREAD(0, STAGE_, 2);                                                           \
         MOE_FMFMA(1);                                                                      \
         MOE_FREAD(1, STAGE_, 3);                                                           \
         MOE_FMFMA(0);                                                                      \
         MOE_FMFMA(1);                                                                      \
     } else {                                                                               \
+        if constexpr (FIRST_) {                                                            \
+            _Pragma("unroll") for (int nj = 0; nj < NN; ++nj)                              \
+                _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                          \
+                    _Pragma("unroll") for (int v = 0; v < Blk<FP8>::VLEN; ++v)             \
+                        acc[nj][mi][v] = 0.f;                                              \
+        }                                                                                  \
         MOE_COMPUTE(STAGE_);                                                               \
     }
     // one K step: multiply LDS stage S_ while step KT_ of CTX_ lands in the other stage
-#define MOE_STEP_DMA(S_, CTX_, KT_)                                                        \
+#define MOE_STEP(S_, CTX_, KT_, FIRST_)                                                    \
     {                                                                                      \
         MOE_DMA_ISSUE(1 - (S_), CTX_, KT_);                                                \
-        MOE_COMPUTE_DMA(S_);                                                               \
-        MOE_ISSUE_ORDER_DMA();                                                             \
+        MOE_COMPUTE_STEP(S_, FIRST_);                                                      \
+        MOE_ISSUE_ORDER();                                                                 \
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                   \
         __syncthreads();                                                                   \
     }
 
     const int KT = a.KT;   // even, >= 2
+    const int stride = 8 * nslots;
     TileCtx cur, nxt;
-    load_ctx<MODE>(cur, a, L, tid);
+    ctx_from_rec<MODE>(cur, a, uniform_rec(a.order[L]), tid);
+    fill_a_off<MODE>(cur, a, tid);
     fill_b_off<MODE, BE>(cur, a, tid);
-    if constexpr (LOADER_DMA) {
-        MOE_DMA_ISSUE(0, cur, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else {
-        MOE_GLOAD(0, cur, 0);
-        MOE_GLOAD(1, cur, 1);
-        MOE_LSTORE(0, 0);
-    }
+    // The record of the tile after the next one is always on its way, and it is moved to scalar
+    // registers right behind a K step's own wait: nothing at a tile's start waits for memory (a
+    // wait there would also wait for the previous tile's stores).
+    int4 rec_v = a.order[min(L + stride, total - 1)];
+    MOE_DMA_ISSUE(0, cur, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int4 rec_s = uniform_rec(rec_v);
     __syncthreads();
 
     int tile_parity = 0;
-    // Invariant at the top of every K-step pair (kt even): LDS stage 0 holds step kt.  Register-
-    // staged loader: register set 1 holds (or is receiving) step kt+1, register set 0 is free.
+    // Invariant at the top of every tile: LDS stage 0 holds its K step 0; rec_s is the next tile's record.
     for (;;) {
-        L += 8 * nslots;
+        L += stride;
         const bool has_next = L < l_end;
-        if (has_next) load_ctx<MODE>(nxt, a, L, tid);
-        else nxt = cur;   // nothing follows: the trailing loads re-read this tile (harmless)
+        if (has_next) ctx_from_rec<MODE>(nxt, a, rec_s, tid);
+        else nxt = cur;   // nothing follows: the trailing load re-reads this tile (harmless)
+        rec_v = a.order[min(L + stride, total - 1)];
         float* row_scale = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES) + (tile_parity << 8);
         if (FP8 && tid < BM) row_scale[tid] = a.sA[min(cur.row0 + tid, cur.row_end - 1)];
         tile_parity ^= 1;   // the buffer is read in this tile's epilogue, many barriers from here
 
-#pragma unroll
-        for (int nj = 0; nj < NN; ++nj)
-#pragma unroll
-            for (int mi = 0; mi < NM; ++mi)
-#pragma unroll
-                for (int v = 0; v < Blk<FP8>::VLEN; ++v) acc[nj][mi][v] = 0.f;
-
-        if constexpr (LOADER_DMA) {
-            for (int kt = 0; kt < KT - 2; kt += 2) {
-                MOE_STEP_DMA(0, cur, kt + 1);
-                MOE_STEP_DMA(1, cur, kt + 2);
-            }
-            // last pair of this tile: the second load is step 0 of the next tile
-            MOE_STEP_DMA(0, cur, KT - 1);
-            fill_b_off<MODE, BE>(nxt, a, tid);
-            MOE_STEP_DMA(1, nxt, 0);
-        } else {
-            for (int kt = 0; kt < KT - 2; kt += 2) {
-                MOE_GLOAD(0, cur, kt + 2);
-                MOE_COMPUTE(0);
-                MOE_LSTORE(1, 1);
-                MOE_ISSUE_ORDER();
-                __syncthreads();
-                MOE_GLOAD(1, cur, kt + 3);
-                MOE_COMPUTE(1);
-                MOE_LSTORE(0, 0);
-                MOE_ISSUE_ORDER();
-                __syncthreads();
-            }
-            // last pair of this tile: its two loads are steps 0 and 1 of the next tile
-            fill_b_off<MODE, BE>(nxt, a, tid);
-            MOE_GLOAD(0, nxt, 0);
-            MOE_COMPUTE(0);
-            MOE_LSTORE(1, 1);
-            MOE_ISSUE_ORDER();
-            __syncthreads();
-            MOE_GLOAD(1, nxt, 1);
-            MOE_COMPUTE(1);
-            MOE_LSTORE(0, 0);
-            MOE_ISSUE_ORDER();
-            __syncthreads();
+        MOE_STEP(0, cur, 1, true);
+        rec_s = uniform_rec(rec_v);
+        for (int kt = 1; kt < KT - 1; kt += 2) {
+            MOE_STEP(1, cur, kt + 1, false);
+            MOE_STEP(0, cur, kt + 2, false);
         }
+        // last step of this tile: its load is step 0 of the next tile
+        if (has_next) {
+            fill_a_off<MODE>(nxt, a, tid);
+            fill_b_off<MODE, BE>(nxt, a, tid);
+        }
+        MOE_STEP(1, nxt, 0, false);
 
         store_tile<MODE, FP8, acc_t>(acc, a, cur, wm, wn, fr, fq, row_scale);
         if (!has_next) break;
         cur = nxt;
     }
-#undef MOE_GLOAD
-#undef MOE_LSTORE
 #undef MOE_COMPUTE
 #undef MOE_LOAD_FRAG8
 #undef MOE_ISSUE_ORDER
-#undef MOE_ISSUE_ORDER_DMA
 #undef MOE_DMA_ISSUE
-#undef MOE_STEP_DMA
-#undef MOE_COMPUTE_DMA
+#undef MOE_STEP
+#undef MOE_COMPUTE_STEP
 #undef MOE_FREAD
 #undef MOE_FMFMA
+#undef MOE_FMFMA_Z
 #undef MOE_SGB
 }
 
@@ -729,15 +670,15 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     char* ws8 = static_cast<char*>(ws);
     int32_t* table = reinterpret_cast<int32_t*>(ws8 + w.table);
     int32_t* first = reinterpret_cast<int32_t*>(ws8 + w.first);
-    int32_t* order_gu = reinterpret_cast<int32_t*>(ws8 + w.order_gu);
-    int32_t* order_dn = reinterpret_cast<int32_t*>(ws8 + w.order_dn);
+    int4* order_gu = reinterpret_cast<int4*>(ws8 + w.order_gu);
+    int4* order_dn = reinterpret_cast<int4*>(ws8 + w.order_dn);
     char* act = act_tap ? static_cast<char*>(act_tap) : ws8 + w.act;
     const int nct_gu = (int)ceil_div64(c.I, 128), nct_dn = (int)ceil_div64(c.H, 256);
     int32_t st = launch_build_tile_table(c, offsets, BM, table, first, s);
     if (st != MOE_OK) return st;
-    st = launch_build_tile_order(c, first, nct_gu, GROUP_ROWS, GROUP_COLS, order_gu, s);
+    st = launch_build_tile_order(c, first, offsets, BM, nct_gu, GROUP_ROWS, GROUP_COLS, order_gu, s);
     if (st != MOE_OK) return st;
-    st = launch_build_tile_order(c, first, nct_dn, GROUP_ROWS, GROUP_COLS, order_dn, s);
+    st = launch_build_tile_order(c, first, offsets, BM, nct_dn, GROUP_ROWS, GROUP_COLS, order_dn, s);
     if (st != MOE_OK) return st;
 
     // one persistent workgroup per compute unit (the 128 KB of LDS allow no second one)
@@ -786,7 +727,6 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     g.sB1 = s_up;
     g.table = table;
     g.order = order_gu;
-    g.offsets = offsets;
     g.C = act;
     g.nct = nct_gu;
     {
@@ -815,7 +755,6 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.sB1 = nullptr;
     d.table = table;
     d.order = order_dn;
-    d.offsets = offsets;
     // y: block-scaled 16-bit codes for the fused call, the same values as float32 for a caller
     // that wants to see y, or the untouched float32 accumulators when the configuration asks
     if (y_codes) {

@@ -45,20 +45,22 @@ int32_t launch_build_tile_table(const moe_config_t& c, const int32_t* offsets, i
     return launch_status();
 }
 
-// Launch order of the output tiles (row tile rt, column tile ct), packed as rt << 8 | ct.
-// Inside one expert, row tiles are taken in groups of `gr` and column tiles in groups of `gc`;
-// a group of (up to) gr x gc tiles is listed row by row before the next column group starts.
-// Workgroups that run at the same time on one XCD therefore cover a compact block of the
-// expert's output and share its token rows and weight rows in that XCD's L2.  An expert with a
-// single row tile degenerates to column-fastest order (all its tiles share the token rows).
+// Launch order of the output tiles: one record (expert, first sorted row, end row, column tile)
+// per launch slot.  Inside one expert, row tiles are taken in groups of `gr` and column tiles in
+// groups of `gc`; a group of (up to) gr x gc tiles is listed row by row before the next column
+// group starts.  Workgroups that run at the same time on one XCD therefore cover a compact block
+// of the expert's output and share its token rows and weight rows in that XCD's L2.  An expert
+// with a single row tile degenerates to column-fastest order (all its tiles share the token rows).
 __global__ __launch_bounds__(256) void build_tile_order_kernel(const int32_t* __restrict__ first,
+                                                              const int32_t* __restrict__ offsets, int bm,
                                                               int nct, int gr, int gc,
-                                                              int32_t* __restrict__ order) {
+                                                              int4* __restrict__ order) {
     const int e = blockIdx.x;
     const int rt0 = first[e];
     const int n = first[e + 1] - rt0;
+    const int row_begin = offsets[e], row_end = offsets[e + 1];
     const int total = n * nct;
-    int32_t* out = order + (size_t)rt0 * nct;
+    int4* out = order + (size_t)rt0 * nct;
     for (int i = threadIdx.x; i < total; i += blockDim.x) {
         const int g = i / (gr * nct);
         const int rem = i - g * gr * nct;
@@ -68,13 +70,14 @@ __global__ __launch_bounds__(256) void build_tile_order_kernel(const int32_t* __
         const int gw = min(gc, nct - cg * gc);
         const int r = rem2 / gw;
         const int c = rem2 - r * gw;
-        out[i] = ((rt0 + g * gr + r) << 8) | (cg * gc + c);
+        const int row0 = row_begin + (g * gr + r) * bm;
+        out[i] = make_int4(e, row0, min(row_end, row0 + bm), cg * gc + c);
     }
 }
 
-int32_t launch_build_tile_order(const moe_config_t& c, const int32_t* first, int nct, int gr, int gc,
-                                int32_t* order, hipStream_t s) {
-    build_tile_order_kernel<<<c.E, 256, 0, s>>>(first, nct, gr, gc, order);
+int32_t launch_build_tile_order(const moe_config_t& c, const int32_t* first, const int32_t* offsets, int bm,
+                                int nct, int gr, int gc, int4* order, hipStream_t s) {
+    build_tile_order_kernel<<<c.E, 256, 0, s>>>(first, offsets, bm, nct, gr, gc, order);
     return launch_status();
 }
 

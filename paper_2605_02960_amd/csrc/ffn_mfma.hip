@@ -165,19 +165,26 @@ __device__ __forceinline__ void fill_a_off(TileCtx& t, const MfmaArgs& a, int ti
         t.a_off[i] = src * a.lda_bytes + lchunk * 16;
     }
 }
-// MFMA block edge: 32 (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x64_f8f6f4).  16 selects
-// v_mfma_f32_16x16x32_bf16 for the bf16 path: faster in a bare MFMA loop, slower in this kernel.
-#ifndef MOE_BF16_BLK
-#define MOE_BF16_BLK 32
+// MFMA block edge of the bf16 kernels: 32 (v_mfma_f32_32x32x16_bf16) or 16
+// (v_mfma_f32_16x16x32_bf16, half the accumulator writes per flop).  Measured on the 235B layer
+// shape: 16 is 3.5 % faster for gate/up (64 K steps per tile) and no faster for down; fp8 uses
+// v_mfma_f32_32x32x64_f8f6f4.
+#ifndef MOE_BF16_BLK_GATE_UP
+#define MOE_BF16_BLK_GATE_UP 16
 #endif
-template <bool FP8>
+#ifndef MOE_BF16_BLK_DOWN
+#define MOE_BF16_BLK_DOWN 32
+#endif
+template <int MODE, bool FP8>
 struct Blk {
-    static constexpr int E = FP8 ? 32 : MOE_BF16_BLK;   // rows / columns of one MFMA block
+    static constexpr int E = FP8 ? 32 : (MODE == MODE_GATE_UP ? MOE_BF16_BLK_GATE_UP : MOE_BF16_BLK_DOWN);   // rows / columns of one MFMA block
     static constexpr int NM = 64 / E;            // blocks along the wave's 64 token rows
     static constexpr int NN = 128 / E;           // blocks along the wave's 128 weight rows
     static constexpr int VLEN = E * E / 64;      // accumulator registers of one block
     static constexpr int NBG = 64 / E;           // gate/up: adjacent output columns per lane
 };
+template <bool FP8>
+using BlkDown = Blk<MODE_DOWN, FP8>;
 
 // Weight row held by LDS row R of the weight tile.  A wave's MFMA blocks are interleaved over
 // its output columns (block nj, lane j <-> column NB*j + nj of a column range, NB blocks per
@@ -226,10 +233,10 @@ __device__ __forceinline__ float quad_max(float v) {
 // 32768), at least 15; code = rint(v * 2^(141-k)), |code| <= 32767.  The rounding is the float32
 // addition of 1.5 * 2^23 (round to nearest even at integer spacing), fused with the exact scaling.
 template <bool FP8, int y_mode, typename ACC>
-__device__ __forceinline__ void store_tile_down_as(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+__device__ __forceinline__ void store_tile_down_as(ACC (&acc)[BlkDown<FP8>::NN][BlkDown<FP8>::NM], const MfmaArgs& a,
                                                    const TileCtx& t, int wm, int wn, int fr, int fq,
                                                    const float* row_scale) {
-    constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN, VLEN = Blk<FP8>::VLEN;
+    constexpr int BE = BlkDown<FP8>::E, NM = BlkDown<FP8>::NM, NN = BlkDown<FP8>::NN, VLEN = BlkDown<FP8>::VLEN;
     constexpr int NGRP = NN / 4;                 // column ranges of 4*BE columns, 4 adjacent columns per lane
     const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
     if (nb >= a.N) return;                       // N is a multiple of 128: the whole wave is in or out
@@ -287,7 +294,7 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[Blk<FP8>::NN][Blk<
 }
 
 template <bool FP8, typename ACC>
-__device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+__device__ __forceinline__ void store_tile_down(ACC (&acc)[BlkDown<FP8>::NN][BlkDown<FP8>::NM], const MfmaArgs& a,
                                                 const TileCtx& t, int wm, int wn, int fr, int fq,
                                                 const float* row_scale) {
     // one copy of the unrolled epilogue per storage form, chosen once per tile
@@ -296,15 +303,15 @@ __device__ __forceinline__ void store_tile_down(ACC (&acc)[Blk<FP8>::NN][Blk<FP8
     else store_tile_down_as<FP8, Y_EXACT_F32, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
 }
 
-template <int MODE, bool FP8, typename ACC>
-__device__ __forceinline__ void store_tile(ACC (&acc)[Blk<FP8>::NN][Blk<FP8>::NM], const MfmaArgs& a,
+template <int MODE, bool FP8, typename ACC, int NN_, int NM_>
+__device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs& a,
                                            const TileCtx& t, int wm, int wn, int fr, int fq,
                                            const float* row_scale) {
     if constexpr (MODE == MODE_DOWN) {
         store_tile_down<FP8, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
     } else {
-        constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, VLEN = Blk<FP8>::VLEN;
-        constexpr int NBG = Blk<FP8>::NBG;
+        constexpr int BE = Blk<MODE, FP8>::E, NM = Blk<MODE, FP8>::NM, VLEN = Blk<MODE, FP8>::VLEN;
+        constexpr int NBG = Blk<MODE, FP8>::NBG;
         constexpr int NPER = NBG;                                     // adjacent columns per lane
         const int n = t.n0 + wn * 64 + NBG * fr;
         if (n >= a.N) return;
@@ -400,7 +407,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 
     // ---- fragment read offsets.  Lane = (fq, fr): fr = row of the MFMA block, fq = which 16-byte
     // (bf16) or 32-byte (fp8) piece of the block's K slice the lane supplies.
-    constexpr int BE = Blk<FP8>::E, NM = Blk<FP8>::NM, NN = Blk<FP8>::NN;
+    constexpr int BE = Blk<MODE, FP8>::E, NM = Blk<MODE, FP8>::NM, NN = Blk<MODE, FP8>::NN;
     constexpr int NG = 64 / BE;                 // lane groups = pieces per K slice
     const int fr = lane % BE, fq = lane / BE;
     const int sw = (fr >> 1) & 7;
@@ -479,8 +486,18 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // Issue order inside one K step, imposed on the compiler's scheduler (which otherwise gathers
     // the LDS reads in blocks of their own): the loads come first (program order), then the
     // fragments of the first K slice, then every MFMA followed by one fragment read of the next slice
-#define MOE_ISSUE_ORDER()                                                              \
-    if constexpr (BE == 32) {                                                              \
+#define MOE_ISSUE_ORDER()                                                                  \
+    if constexpr (!FP8 && BE == 16) {                                                      \
+        MOE_SGB(0x100, NM + NN);                                                           \
+        _Pragma("unroll") for (int g = 0; g < 3; ++g) {                                    \
+            _Pragma("unroll") for (int j = 0; j < NN / 2; ++j) {                           \
+                MOE_SGB(0x008, 1);                                                         \
+                MOE_SGB(0x100, 1);                                                         \
+            }                                                                              \
+            MOE_SGB(0x008, NM * NN / 2 - NN / 2);                                          \
+        }                                                                                  \
+        MOE_SGB(0x008, NM * NN / 2);                                                       \
+    } else if constexpr (BE == 32) {                                                       \
         constexpr int NMF = NM * NN, NKK = FP8 ? 2 : 4, RPF = FP8 ? 2 : 1;                 \
         constexpr int NRS = NM + NN;                                                       \
         MOE_SGB(0x100, NRS * RPF);                                                         \
@@ -516,6 +533,30 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                              \
                 acc[nj][mi] = mfma_bf16(fa##BUF_[mi], fb##BUF_[nj], acc_t{});              \
     }
+    // 16x16x32 blocks: a K step is two slices; a slice's weight fragments are handled in two
+    // halves (blocks 0..NN/2-1 and the rest) so that two half buffers and two token-fragment
+    // buffers suffice to keep the reads one group of 16 MFMAs ahead
+#define MOE_FREAD_A16(DST_, STAGE_, KK_)                                                   \
+    {                                                                                      \
+        const char* st = smem + (STAGE_) * STAGE_BYTES;                                    \
+        _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) DST_[mi] =                       \
+            *reinterpret_cast<const bf16x8*>(st + xa_row + mi * BE * ROW_BYTES + frag_off[KK_]); \
+    }
+#define MOE_FREAD_B16(HALF_, STAGE_, KK_)                                                  \
+    {                                                                                      \
+        const char* st = smem + (STAGE_) * STAGE_BYTES;                                    \
+        _Pragma("unroll") for (int q = 0; q < NN / 2; ++q) fb0[(HALF_) * (NN / 2) + q] =   \
+            *reinterpret_cast<const bf16x8*>(st + wb_base + wb_off((HALF_) * (NN / 2) + q) + frag_off[KK_]); \
+    }
+#define MOE_FMFMA16(FA_, HALF_, Z_)                                                        \
+    {                                                                                      \
+        _Pragma("unroll") for (int q = 0; q < NN / 2; ++q)                                 \
+            _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) {                            \
+                constexpr int njh = (HALF_) * (NN / 2);                                    \
+                if constexpr (Z_) acc[njh + q][mi] = mfma_bf16(FA_[mi], fb0[njh + q], acc_t{}); \
+                else acc[njh + q][mi] = mfma_bf16(FA_[mi], fb0[njh + q], acc[njh + q][mi]); \
+            }                                                                              \
+    }
 #define MOE_COMPUTE_STEP(STAGE_, FIRST_)                                                   \
     if constexpr (!FP8 && BE == 32) {                                                      \
         MOE_FREAD(0, STAGE_, 0);                                                           \
@@ -526,11 +567,22 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         MOE_FREAD(1, STAGE_, 3);                                                           \
         MOE_FMFMA(0);                                                                      \
         MOE_FMFMA(1);                                                                      \
+    } else if constexpr (!FP8 && BE == 16) {                                               \
+        MOE_FREAD_A16(fa0, STAGE_, 0);                                                     \
+        MOE_FREAD_B16(0, STAGE_, 0);                                                       \
+        MOE_FREAD_B16(1, STAGE_, 0);                                                       \
+        MOE_FMFMA16(fa0, 0, FIRST_);                                                       \
+        MOE_FREAD_A16(fa1, STAGE_, 1);                                                     \
+        MOE_FREAD_B16(0, STAGE_, 1);                                                       \
+        MOE_FMFMA16(fa0, 1, FIRST_);                                                       \
+        MOE_FREAD_B16(1, STAGE_, 1);                                                       \
+        MOE_FMFMA16(fa1, 0, false);                                                        \
+        MOE_FMFMA16(fa1, 1, false);                                                        \
     } else {                                                                               \
         if constexpr (FIRST_) {                                                            \
             _Pragma("unroll") for (int nj = 0; nj < NN; ++nj)                              \
                 _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                          \
-                    _Pragma("unroll") for (int v = 0; v < Blk<FP8>::VLEN; ++v)             \
+                    _Pragma("unroll") for (int v = 0; v < Blk<MODE, FP8>::VLEN; ++v)             \
                         acc[nj][mi][v] = 0.f;                                              \
         }                                                                                  \
         MOE_COMPUTE(STAGE_);                                                               \
@@ -598,6 +650,9 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_FREAD
 #undef MOE_FMFMA
 #undef MOE_FMFMA_Z
+#undef MOE_FREAD_A16
+#undef MOE_FREAD_B16
+#undef MOE_FMFMA16
 #undef MOE_SGB
 }
 

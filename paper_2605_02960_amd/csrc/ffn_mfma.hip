@@ -10,10 +10,11 @@
 // 256 weight rows x one K step of 128 bytes per row (64 bf16 or 128 fp8).  For gate/up the 256
 // weight rows are 128 rows of Wg and the same 128 rows of Wu, so that a lane holds g and u of one
 // output element side by side.  Each wave owns 64 rows x 128 weight rows = 2 x 4 MFMA blocks of
-// 32 x 32 (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x64_f8f6f4; 128 accumulator registers).
+// 32 x 32 (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x64_f8f6f4) or 4 x 8 blocks of 16 x 16
+// (v_mfma_f32_16x16x32_bf16); 128 accumulator registers either way.
 // The token fragment is the MFMA "A" operand and the weight fragment the "B" operand; the
-// wave's weight rows are interleaved over its output columns so that a lane ends up with 2
-// (gate/up) or 4 (down) adjacent output columns and 32 lanes store whole 128-byte lines.
+// wave's weight rows are interleaved over its output columns so that a lane ends up with 2 or 4
+// adjacent output columns and the lanes of one block row store whole 128-byte lines.
 //
 // fp8 (e4m3 codes, float scales per token row and per output channel): the accumulators hold sums
 // of code products and the scales are applied in the epilogue.
@@ -31,9 +32,14 @@
 // top of step k and awaited (vmcnt(0) + barrier) at its end.  A register-staged loader (global
 // load to registers, LDS store one K step later, prefetch distance 2) is kept behind MOE_DMA=0.
 //
-// Issue order.  bf16: the fragments of K slice s+1 are read into the second of two fragment
-// register sets before the MFMAs of slice s are issued, and scheduling group barriers put one
-// fragment read behind each MFMA, so the matrix pipe never waits for LDS.  fp8 keeps one set.
+// MFMA blocks.  Gate/up (bf16) multiplies 16 x 16 x 32 blocks (v_mfma_f32_16x16x32_bf16: half the
+// accumulator writes per flop of the 32 x 32 x 16 form, which shows on a part that is limited by
+// power: +3.5 %); down (24 K steps per tile at I = 1536) gains nothing from them and keeps 32 x 32.
+//
+// Issue order.  bf16: the fragments of the next K slice (32 x 32 blocks) or of the next group of
+// 16 MFMAs (16 x 16 blocks) are read into a second set of fragment registers before the MFMAs of
+// the current one are issued, and scheduling group barriers spread those reads between the
+// MFMAs, so the matrix pipe never waits for LDS.  fp8 keeps one set.
 //
 // Pipeline.  The kernel is persistent (one workgroup per CU): the load that a tile's last K step
 // issues is the first K step of the workgroup's NEXT tile, so consecutive tiles chain without
@@ -485,16 +491,18 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
     // Issue order inside one K step, imposed on the compiler's scheduler (which otherwise gathers
     // the LDS reads in blocks of their own): the loads come first (program order), then the
-    // fragments of the first K slice, then every MFMA followed by one fragment read of the next slice
+    // fragments of the first K slice; after that, 32x32 blocks: every MFMA followed by one fragment
+    // read of the next slice; 16x16 blocks: three groups of 16 MFMAs with one of the next group's 4
+    // fragment reads behind every third MFMA (measured best of six spacings), then the last group.
 #define MOE_ISSUE_ORDER()                                                                  \
     if constexpr (!FP8 && BE == 16) {                                                      \
         MOE_SGB(0x100, NM + NN);                                                           \
         _Pragma("unroll") for (int g = 0; g < 3; ++g) {                                    \
             _Pragma("unroll") for (int j = 0; j < NN / 2; ++j) {                           \
-                MOE_SGB(0x008, 1);                                                         \
+                MOE_SGB(0x008, 3);                                                         \
                 MOE_SGB(0x100, 1);                                                         \
             }                                                                              \
-            MOE_SGB(0x008, NM * NN / 2 - NN / 2);                                          \
+            MOE_SGB(0x008, NM * NN / 2 - 3 * NN / 2);                                      \
         }                                                                                  \
         MOE_SGB(0x008, NM * NN / 2);                                                       \
     } else if constexpr (BE == 32) {                                                       \

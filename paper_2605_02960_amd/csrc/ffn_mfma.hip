@@ -172,25 +172,16 @@ __device__ __forceinline__ void fill_a_off(TileCtx& t, const MfmaArgs& a, int ti
     }
 }
 // MFMA block edge of the bf16 kernels: 32 (v_mfma_f32_32x32x16_bf16) or 16
-// (v_mfma_f32_16x16x32_bf16, half the accumulator writes per flop).  Measured on the 235B layer
-// shape: 16 is 3.5 % faster for gate/up (64 K steps per tile) and no faster for down; fp8 uses
+// (v_mfma_f32_16x16x32_bf16, half the accumulator writes per flop); a template parameter of the
+// kernel, chosen at launch from the number of K steps per tile.  fp8 uses
 // v_mfma_f32_32x32x64_f8f6f4.
-#ifndef MOE_BF16_BLK_GATE_UP
-#define MOE_BF16_BLK_GATE_UP 16
-#endif
-#ifndef MOE_BF16_BLK_DOWN
-#define MOE_BF16_BLK_DOWN 32
-#endif
-template <int MODE, bool FP8>
+template <bool FP8, int BLK>
 struct Blk {
-    static constexpr int E = FP8 ? 32 : (MODE == MODE_GATE_UP ? MOE_BF16_BLK_GATE_UP : MOE_BF16_BLK_DOWN);   // rows / columns of one MFMA block
+    static constexpr int E = FP8 ? 32 : BLK;     // rows / columns of one MFMA block
     static constexpr int NM = 64 / E;            // blocks along the wave's 64 token rows
     static constexpr int NN = 128 / E;           // blocks along the wave's 128 weight rows
     static constexpr int VLEN = E * E / 64;      // accumulator registers of one block
-    static constexpr int NBG = 64 / E;           // gate/up: adjacent output columns per lane
 };
-template <bool FP8>
-using BlkDown = Blk<MODE_DOWN, FP8>;
 
 // Weight row held by LDS row R of the weight tile.  A wave's MFMA blocks are interleaved over
 // its output columns (block nj, lane j <-> column NB*j + nj of a column range, NB blocks per
@@ -238,11 +229,11 @@ __device__ __forceinline__ float quad_max(float v) {
 // largest magnitude, k = biased exponent of amax (one higher if amax * 2^(141-k) would round to
 // 32768), at least 15; code = rint(v * 2^(141-k)), |code| <= 32767.  The rounding is the float32
 // addition of 1.5 * 2^23 (round to nearest even at integer spacing), fused with the exact scaling.
-template <bool FP8, int y_mode, typename ACC>
-__device__ __forceinline__ void store_tile_down_as(ACC (&acc)[BlkDown<FP8>::NN][BlkDown<FP8>::NM], const MfmaArgs& a,
+template <bool FP8, int y_mode, typename ACC, int NN, int NM>
+__device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const MfmaArgs& a,
                                                    const TileCtx& t, int wm, int wn, int fr, int fq,
                                                    const float* row_scale) {
-    constexpr int BE = BlkDown<FP8>::E, NM = BlkDown<FP8>::NM, NN = BlkDown<FP8>::NN, VLEN = BlkDown<FP8>::VLEN;
+    constexpr int BE = 64 / NM, VLEN = BE * BE / 64;
     constexpr int NGRP = NN / 4;                 // column ranges of 4*BE columns, 4 adjacent columns per lane
     const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
     if (nb >= a.N) return;                       // N is a multiple of 128: the whole wave is in or out
@@ -299,14 +290,14 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[BlkDown<FP8>::NN][
     }
 }
 
-template <bool FP8, typename ACC>
-__device__ __forceinline__ void store_tile_down(ACC (&acc)[BlkDown<FP8>::NN][BlkDown<FP8>::NM], const MfmaArgs& a,
+template <bool FP8, typename ACC, int NN, int NM>
+__device__ __forceinline__ void store_tile_down(ACC (&acc)[NN][NM], const MfmaArgs& a,
                                                 const TileCtx& t, int wm, int wn, int fr, int fq,
                                                 const float* row_scale) {
     // one copy of the unrolled epilogue per storage form, chosen once per tile
-    if (a.y_mode == Y_BLOCK16) store_tile_down_as<FP8, Y_BLOCK16, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
-    else if (a.y_mode == Y_BLOCK16_AS_F32) store_tile_down_as<FP8, Y_BLOCK16_AS_F32, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
-    else store_tile_down_as<FP8, Y_EXACT_F32, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
+    if (a.y_mode == Y_BLOCK16) store_tile_down_as<FP8, Y_BLOCK16>(acc, a, t, wm, wn, fr, fq, row_scale);
+    else if (a.y_mode == Y_BLOCK16_AS_F32) store_tile_down_as<FP8, Y_BLOCK16_AS_F32>(acc, a, t, wm, wn, fr, fq, row_scale);
+    else store_tile_down_as<FP8, Y_EXACT_F32>(acc, a, t, wm, wn, fr, fq, row_scale);
 }
 
 template <int MODE, bool FP8, typename ACC, int NN_, int NM_>
@@ -314,10 +305,10 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs&
                                            const TileCtx& t, int wm, int wn, int fr, int fq,
                                            const float* row_scale) {
     if constexpr (MODE == MODE_DOWN) {
-        store_tile_down<FP8, ACC>(acc, a, t, wm, wn, fr, fq, row_scale);
+        store_tile_down<FP8>(acc, a, t, wm, wn, fr, fq, row_scale);
     } else {
-        constexpr int BE = Blk<MODE, FP8>::E, NM = Blk<MODE, FP8>::NM, VLEN = Blk<MODE, FP8>::VLEN;
-        constexpr int NBG = Blk<MODE, FP8>::NBG;
+        constexpr int NM = NM_, BE = 64 / NM, VLEN = BE * BE / 64;
+        constexpr int NBG = 64 / BE;              // adjacent output columns per lane
         constexpr int NPER = NBG;                                     // adjacent columns per lane
         const int n = t.n0 + wn * 64 + NBG * fr;
         if (n >= a.N) return;
@@ -392,7 +383,7 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const ch
                  : "memory", "m0");
 }
 
-template <int MODE, bool FP8>
+template <int MODE, bool FP8, int BLK>
 __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -413,7 +404,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 
     // ---- fragment read offsets.  Lane = (fq, fr): fr = row of the MFMA block, fq = which 16-byte
     // (bf16) or 32-byte (fp8) piece of the block's K slice the lane supplies.
-    constexpr int BE = Blk<MODE, FP8>::E, NM = Blk<MODE, FP8>::NM, NN = Blk<MODE, FP8>::NN;
+    constexpr int BE = Blk<FP8, BLK>::E, NM = Blk<FP8, BLK>::NM, NN = Blk<FP8, BLK>::NN;
     constexpr int NG = 64 / BE;                 // lane groups = pieces per K slice
     const int fr = lane % BE, fq = lane / BE;
     const int sw = (fr >> 1) & 7;
@@ -590,7 +581,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         if constexpr (FIRST_) {                                                            \
             _Pragma("unroll") for (int nj = 0; nj < NN; ++nj)                              \
                 _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                          \
-                    _Pragma("unroll") for (int v = 0; v < Blk<MODE, FP8>::VLEN; ++v)             \
+                    _Pragma("unroll") for (int v = 0; v < Blk<FP8, BLK>::VLEN; ++v)              \
                         acc[nj][mi][v] = 0.f;                                              \
         }                                                                                  \
         MOE_COMPUTE(STAGE_);                                                               \
@@ -645,7 +636,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         }
         MOE_STEP(1, nxt, 0, false);
 
-        store_tile<MODE, FP8, acc_t>(acc, a, cur, wm, wn, fr, fq, row_scale);
+        store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fq, row_scale);
         if (!has_next) break;
         cur = nxt;
     }
@@ -697,14 +688,28 @@ __global__ __launch_bounds__(256) void gather_row_scales_kernel(const float* __r
     if (p < P) sxp[p] = sx[perm[p] / K];
 }
 
+// bf16: 16 x 16 blocks pay when a tile has enough K steps for the K loop to dominate (measured:
+// +3.5 % at 64 steps, +2 % at 32, +2.5 % at 24, -2 % at 12)
+inline bool use_blk16(int kt) { return kt >= 16; }
+
+template <int MODE>
+int32_t launch_kernel(bool fp8, const MfmaArgs& args, dim3 grid, hipStream_t s) {
+    if (fp8) ffn_mfma_kernel<MODE, true, 32><<<grid, THREADS, LDS_BYTES, s>>>(args);
+    else if (use_blk16(args.KT)) ffn_mfma_kernel<MODE, false, 16><<<grid, THREADS, LDS_BYTES, s>>>(args);
+    else ffn_mfma_kernel<MODE, false, 32><<<grid, THREADS, LDS_BYTES, s>>>(args);
+    return launch_status();
+}
+
+template <int MODE, bool FP8, int BLK>
+bool allow_lds() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE, FP8, BLK>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess;
+}
 template <bool FP8>
 int32_t set_kernel_attributes() {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_GATE_UP, FP8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE_DOWN, FP8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-        return MOE_ERR_LAUNCH_FAILED;
-    return MOE_OK;
+    bool ok = allow_lds<MODE_GATE_UP, FP8, 32>() && allow_lds<MODE_DOWN, FP8, 32>();
+    if (!FP8) ok = ok && allow_lds<MODE_GATE_UP, false, 16>() && allow_lds<MODE_DOWN, false, 16>();
+    return ok ? MOE_OK : MOE_ERR_LAUNCH_FAILED;
 }
 
 }  // namespace
@@ -794,8 +799,7 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     g.nct = nct_gu;
     {
         KernelBracket kb(MOE_KERNEL_GATE_UP, s);
-        if (fp8) ffn_mfma_kernel<MODE_GATE_UP, true><<<grid, THREADS, LDS_BYTES, s>>>(g);
-        else ffn_mfma_kernel<MODE_GATE_UP, false><<<grid, THREADS, LDS_BYTES, s>>>(g);
+        launch_kernel<MODE_GATE_UP>(fp8, g, grid, s);
     }
     const char* a_dn = act;
     if (fp8) {   // per-row e4m3 of the bf16 activations
@@ -832,8 +836,7 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.nct = nct_dn;
     {
         KernelBracket kb(MOE_KERNEL_DOWN, s);
-        if (fp8) ffn_mfma_kernel<MODE_DOWN, true><<<grid, THREADS, LDS_BYTES, s>>>(d);
-        else ffn_mfma_kernel<MODE_DOWN, false><<<grid, THREADS, LDS_BYTES, s>>>(d);
+        launch_kernel<MODE_DOWN>(fp8, d, grid, s);
     }
     return launch_status();
 }

@@ -226,6 +226,26 @@ def test_bf16_group_sizes_around_tile_edges():
     _bf16_checks(w, d, g, cfg, r, info, None)
 
 
+@pytest.mark.parametrize("T,H,E,K,I,flags", [
+    (700, 1024, 6, 2, 1152, 0),                  # 16 and 18 K steps per tile: both GEMMs on 16 x 16 x 32 blocks
+    (523, 1152, 5, 3, 1024, moe.FLAG_Y_F32),     # same, float32 y
+    (300, 1024, 3, 1, 896, 0),                   # gate/up on 16 x 16 blocks, down (14 K steps) on 32 x 32
+], ids=["blk16_both", "blk16_both_yf32", "blk16_gate_up_only"])
+def test_bf16_long_contraction_small_batch(T, H, E, K, I, flags):
+    """Contractions long enough for the kernels to choose 16 x 16 x 32 MFMA blocks (16 or more K
+    steps of 64 per tile), at a size where every token is checked against the oracle: ragged
+    groups, tiles with one to three row blocks, both storage forms of y, fused == staged."""
+    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name=f"bf16_longk_{T}_{H}_{E}_{K}_{I}_{flags}", T=T, H=H, E=E, K=K, I=I)
+    d = workloads.generate(w)
+    g = gu.upload(d)
+    cfg = gu.config_for(w, flags=flags)
+    print(f"case {w.name} flags={flags}", flush=True)
+    r = gu.run_staged(cfg, g)
+    info = gu.check_routing_and_grouping(cfg, d, r)
+    _bf16_checks(w, d, g, cfg, r, info, None)
+    assert torch.equal(_fused(cfg, g), r["out"])
+
+
 def test_bf16_out_is_rounded_f32_out():
     w = workloads.scaled(workloads.QWEN3_8K, name="bf16_out", T=300, H=256, E=16, K=4, I=128)
     d = workloads.generate(w)

@@ -64,6 +64,11 @@ constexpr int TILE_BYTES = 256 * ROW_BYTES;         // 32 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;         // tokens + weights
 constexpr int THREADS = 512;
 constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * 256 * 4;   // + two buffers of 256 row scales (fp8)
+// bf16: three token-tile slots and two weight-tile slots, all of the 160 KB (see the kernel)
+#ifndef MOE_RING
+#define MOE_RING 1
+#endif
+constexpr int LDS_BYTES_RING = 5 * TILE_BYTES;
 #ifndef MOE_GROUP_ROWS
 #define MOE_GROUP_ROWS 8
 #define MOE_GROUP_COLS 4
@@ -427,6 +432,25 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     typedef typename std::conditional<BE == 32, f32x16, f32x4>::type acc_t;
     acc_t acc[NN][NM];
 
+    // ---- LDS slots.  fp8: two stages of (token tile, weight tile).  bf16 (RING): three token-tile
+    // slots [0, 3) and two weight-tile slots [3, 5) of 32 KB: the token tile of K step k+2 and the
+    // weight tile of step k+1 are requested at the top of step k (weights first), and the step's
+    // end waits for all but the last four requests, i.e. for the weight tile of step k+1 (the
+    // token tile of step k+1 is a step older).  Requests are served in issue order.
+    constexpr bool RING = !FP8 && MOE_RING != 0;
+    constexpr int NKK = FP8 ? 4 : 8 / NG;       // distinct fragment offsets per K step
+    uint32_t ad_a[NKK], ad_b[NKK];              // RING: byte offsets in LDS of the lane's fragments in the slots being read
+    int a_rd = 0, b_rd = 0;                     // RING: slots that hold the current K step
+    if constexpr (RING) {
+#pragma unroll
+        for (int c = 0; c < NKK; ++c) {
+            ad_a[c] = xa_row + frag_off[c];
+            ad_b[c] = 3 * TILE_BYTES + (wb_base - TILE_BYTES) + frag_off[c];
+        }
+    }
+#define MOE_A_PTR(STAGE_, KK_) (RING ? smem + ad_a[KK_] : smem + (STAGE_) * STAGE_BYTES + xa_row + frag_off[KK_])
+#define MOE_B_PTR(STAGE_, KK_) (RING ? smem + ad_b[KK_] : smem + (STAGE_) * STAGE_BYTES + wb_base + frag_off[KK_])
+
 #define MOE_LOAD_FRAG8(PTR_, KK_) load_frag8((PTR_), frag_off[(KK_) * 2], frag_off[(KK_) * 2 + 1])
 #define MOE_COMPUTE(STAGE_)                                                               \
     {                                                                                     \
@@ -513,11 +537,10 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     bf16x8 fa0[NM], fb0[NN], fa1[NM], fb1[NN];
 #define MOE_FREAD(BUF_, STAGE_, KK_)                                                       \
     {                                                                                      \
-        const char* st = smem + (STAGE_) * STAGE_BYTES;                                    \
         _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) fa##BUF_[mi] =                   \
-            *reinterpret_cast<const bf16x8*>(st + xa_row + mi * BE * ROW_BYTES + frag_off[KK_]); \
+            *reinterpret_cast<const bf16x8*>(MOE_A_PTR(STAGE_, KK_) + mi * BE * ROW_BYTES); \
         _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) fb##BUF_[nj] =                   \
-            *reinterpret_cast<const bf16x8*>(st + wb_base + wb_off(nj) + frag_off[KK_]);   \
+            *reinterpret_cast<const bf16x8*>(MOE_B_PTR(STAGE_, KK_) + wb_off(nj));         \
     }
 #define MOE_FMFMA(BUF_)                                                                    \
     {                                                                                      \
@@ -537,15 +560,13 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // buffers suffice to keep the reads one group of 16 MFMAs ahead
 #define MOE_FREAD_A16(DST_, STAGE_, KK_)                                                   \
     {                                                                                      \
-        const char* st = smem + (STAGE_) * STAGE_BYTES;                                    \
         _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) DST_[mi] =                       \
-            *reinterpret_cast<const bf16x8*>(st + xa_row + mi * BE * ROW_BYTES + frag_off[KK_]); \
+            *reinterpret_cast<const bf16x8*>(MOE_A_PTR(STAGE_, KK_) + mi * BE * ROW_BYTES); \
     }
 #define MOE_FREAD_B16(HALF_, STAGE_, KK_)                                                  \
     {                                                                                      \
-        const char* st = smem + (STAGE_) * STAGE_BYTES;                                    \
         _Pragma("unroll") for (int q = 0; q < NN / 2; ++q) fb0[(HALF_) * (NN / 2) + q] =   \
-            *reinterpret_cast<const bf16x8*>(st + wb_base + wb_off((HALF_) * (NN / 2) + q) + frag_off[KK_]); \
+            *reinterpret_cast<const bf16x8*>(MOE_B_PTR(STAGE_, KK_) + wb_off((HALF_) * (NN / 2) + q)); \
     }
 #define MOE_FMFMA16(FA_, HALF_, Z_)                                                        \
     {                                                                                      \
@@ -596,6 +617,48 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         __syncthreads();                                                                   \
     }
 
+    // RING: one operand tile of K step KT_ of CTX_ into slot SLOT_ (4 requests per wave)
+#define MOE_DMA_A(SLOT_, CTX_, KT_)                                                        \
+    {                                                                                      \
+        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                   \
+        const char* abase = uniform_ptr(                                                   \
+            (MODE == MODE_GATE_UP) ? a.A : a.A + (size_t)CTX_.row0 * a.lda_bytes);         \
+        const uint32_t st = __builtin_amdgcn_readfirstlane(                                \
+            lds_base + (uint32_t)(SLOT_) * TILE_BYTES + dma_row0);                         \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+            dma16(st + i * 8 * ROW_BYTES, CTX_.a_off[i] + kb, abase);                      \
+    }
+#define MOE_DMA_B(SLOT_, CTX_, KT_)                                                        \
+    {                                                                                      \
+        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                   \
+        const char* bbase =                                                                \
+            uniform_ptr((MODE == MODE_DOWN || wave_u < 4) ? CTX_.b0e : CTX_.b1e);          \
+        const uint32_t st = __builtin_amdgcn_readfirstlane(                                \
+            lds_base + (uint32_t)(3 + (SLOT_)) * TILE_BYTES + dma_row0);                   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+            dma16(st + i * 8 * ROW_BYTES, CTX_.b_off[i] + kb, bbase);                      \
+    }
+    // RING, one K step: request the weight tile of step KTB_ of CB_ (the next step) and the token
+    // tile of step KTA_ of CA_ (the step after), multiply the current slots, wait for everything
+    // but the token tile just requested, move on to the next slots
+#define MOE_RSTEP(CB_, KTB_, CA_, KTA_, FIRST_)                                            \
+    {                                                                                      \
+        MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                                                    \
+        MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
+        MOE_COMPUTE_STEP(0, FIRST_);                                                       \
+        MOE_ISSUE_ORDER();                                                                 \
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
+        __syncthreads();                                                                   \
+        const uint32_t da = a_rd == 2 ? (uint32_t)(-2 * TILE_BYTES) : (uint32_t)TILE_BYTES; \
+        const uint32_t db = b_rd == 1 ? (uint32_t)(-TILE_BYTES) : (uint32_t)TILE_BYTES;    \
+        a_rd = a_rd == 2 ? 0 : a_rd + 1;                                                   \
+        b_rd ^= 1;                                                                         \
+        _Pragma("unroll") for (int c = 0; c < NKK; ++c) {                                  \
+            ad_a[c] += da;                                                                 \
+            ad_b[c] += db;                                                                 \
+        }                                                                                  \
+    }
+
     const int KT = a.KT;   // even, >= 2
     const int stride = 8 * nslots;
     TileCtx cur, nxt;
@@ -606,7 +669,13 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // registers right behind a K step's own wait: nothing at a tile's start waits for memory (a
     // wait there would also wait for the previous tile's stores).
     int4 rec_v = a.order[min(L + stride, total - 1)];
-    MOE_DMA_ISSUE(0, cur, 0);
+    if constexpr (RING) {
+        MOE_DMA_A(0, cur, 0);
+        MOE_DMA_B(0, cur, 0);
+        MOE_DMA_A(1, cur, 1);
+    } else {
+        MOE_DMA_ISSUE(0, cur, 0);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int4 rec_s = uniform_rec(rec_v);
     __syncthreads();
@@ -623,21 +692,50 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         if (FP8 && tid < BM) row_scale[tid] = a.sA[min(cur.row0 + tid, cur.row_end - 1)];
         tile_parity ^= 1;   // the buffer is read in this tile's epilogue, many barriers from here
 
-        MOE_STEP(0, cur, 1, true);
-        rec_s = uniform_rec(rec_v);
-        for (int kt = 1; kt < KT - 1; kt += 2) {
-            MOE_STEP(1, cur, kt + 1, false);
-            MOE_STEP(0, cur, kt + 2, false);
+        if constexpr (RING) {
+            // Invariant at the top of K step k: token slot a_rd holds step k, the next token slot
+            // holds (or is receiving) step k+1, weight slot b_rd holds step k.
+            if (KT > 2) {
+                MOE_RSTEP(cur, 1, cur, 2, true);
+                rec_s = uniform_rec(rec_v);
+                for (int kt = 1; kt < KT - 2; ++kt) MOE_RSTEP(cur, kt + 1, cur, kt + 2, false);
+                if (has_next) {
+                    fill_a_off<MODE>(nxt, a, tid);
+                    fill_b_off<MODE, BE>(nxt, a, tid);
+                }
+                // last two steps of this tile: their requests reach into the next tile
+                MOE_RSTEP(cur, KT - 1, nxt, 0, false);
+                MOE_RSTEP(nxt, 0, nxt, 1, false);
+            } else {
+                if (has_next) {
+                    fill_a_off<MODE>(nxt, a, tid);
+                    fill_b_off<MODE, BE>(nxt, a, tid);
+                }
+                MOE_RSTEP(cur, 1, nxt, 0, true);
+                rec_s = uniform_rec(rec_v);
+                MOE_RSTEP(nxt, 0, nxt, 1, false);
+            }
+        } else {
+            MOE_STEP(0, cur, 1, true);
+            rec_s = uniform_rec(rec_v);
+            for (int kt = 1; kt < KT - 1; kt += 2) {
+                MOE_STEP(1, cur, kt + 1, false);
+                MOE_STEP(0, cur, kt + 2, false);
+            }
+            // last step of this tile: its load is step 0 of the next tile
+            if (has_next) {
+                fill_a_off<MODE>(nxt, a, tid);
+                fill_b_off<MODE, BE>(nxt, a, tid);
+            }
+            MOE_STEP(1, nxt, 0, false);
         }
-        // last step of this tile: its load is step 0 of the next tile
-        if (has_next) {
-            fill_a_off<MODE>(nxt, a, tid);
-            fill_b_off<MODE, BE>(nxt, a, tid);
-        }
-        MOE_STEP(1, nxt, 0, false);
 
         store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fq, row_scale);
-        if (!has_next) break;
+        if (!has_next) {
+            // the last step's token-tile requests are still on their way into this workgroup's LDS
+            if constexpr (RING) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            break;
+        }
         cur = nxt;
     }
 #undef MOE_COMPUTE
@@ -645,6 +743,11 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_ISSUE_ORDER
 #undef MOE_DMA_ISSUE
 #undef MOE_STEP
+#undef MOE_RSTEP
+#undef MOE_DMA_A
+#undef MOE_DMA_B
+#undef MOE_A_PTR
+#undef MOE_B_PTR
 #undef MOE_COMPUTE_STEP
 #undef MOE_FREAD
 #undef MOE_FMFMA
@@ -694,16 +797,18 @@ inline bool use_blk16(int kt) { return kt >= 16; }
 
 template <int MODE>
 int32_t launch_kernel(bool fp8, const MfmaArgs& args, dim3 grid, hipStream_t s) {
+    constexpr int LDS_BF16 = MOE_RING != 0 ? LDS_BYTES_RING : LDS_BYTES;
     if (fp8) ffn_mfma_kernel<MODE, true, 32><<<grid, THREADS, LDS_BYTES, s>>>(args);
-    else if (use_blk16(args.KT)) ffn_mfma_kernel<MODE, false, 16><<<grid, THREADS, LDS_BYTES, s>>>(args);
-    else ffn_mfma_kernel<MODE, false, 32><<<grid, THREADS, LDS_BYTES, s>>>(args);
+    else if (use_blk16(args.KT)) ffn_mfma_kernel<MODE, false, 16><<<grid, THREADS, LDS_BF16, s>>>(args);
+    else ffn_mfma_kernel<MODE, false, 32><<<grid, THREADS, LDS_BF16, s>>>(args);
     return launch_status();
 }
 
 template <int MODE, bool FP8, int BLK>
 bool allow_lds() {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE, FP8, BLK>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess;
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (!FP8 && MOE_RING != 0) ? LDS_BYTES_RING : LDS_BYTES) == hipSuccess;
 }
 template <bool FP8>
 int32_t set_kernel_attributes() {

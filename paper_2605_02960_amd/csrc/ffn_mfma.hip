@@ -21,29 +21,35 @@
 //
 // LDS.  A tile is [256 rows][128 bytes] in 8 chunks of 16 bytes per row; chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which makes the 16-byte fragment reads of the MFMA
-// operands free of bank conflicts.  Two stages (2 x 64 KB) are double-buffered with one barrier
-// per K step.
+// operands free of bank conflicts.  One barrier per K step.  fp8: two stages of (token tile,
+// weight tile), 2 x 64 KB, plus the row scales.  bf16: five slots of 32 KB, all of the CU's 160 KB:
+// three for token tiles and two for weight tiles.
 //
 // Loader.  The operand tiles go from global memory straight into LDS (global_load_lds_dwordx4:
 // 16 bytes per lane, full 128-byte lines per row, no staging registers and no LDS store
 // instructions).  The instruction writes lane l at LDS base + 16 l, so the swizzle is applied on
 // the global side (the lane that fills position c' of row r fetches chunk c' ^ ((r >> 1) & 7)).
-// Rows of x are gathered through the lane offsets.  The tile for K step k+1 is requested at the
-// top of step k and awaited (vmcnt(0) + barrier) at its end.  A register-staged loader (global
-// load to registers, LDS store one K step later, prefetch distance 2) is kept behind MOE_DMA=0.
+// Rows of x are gathered through the lane offsets.  fp8: both tiles of K step k+1 are requested
+// at the top of step k and awaited (vmcnt(0) + barrier) at its end.  bf16: the top of step k
+// requests the weight tile of step k+1 and then the token tile of step k+2; the step's end waits
+// for all but the four youngest requests (requests are served in issue order), so the token
+// tiles, whose rows are gathered from all over x, have two steps to arrive (+2.4 %).
 //
-// MFMA blocks.  Gate/up (bf16) multiplies 16 x 16 x 32 blocks (v_mfma_f32_16x16x32_bf16: half the
-// accumulator writes per flop of the 32 x 32 x 16 form, which shows on a part that is limited by
-// power: +3.5 %); down (24 K steps per tile at I = 1536) gains nothing from them and keeps 32 x 32.
+// MFMA blocks.  bf16 kernels whose tiles have 16 or more K steps multiply 16 x 16 x 32 blocks
+// (v_mfma_f32_16x16x32_bf16: half the accumulator writes per flop of the 32 x 32 x 16 form, which
+// shows on a part that is limited by power: +3.5 % at 64 K steps per tile, -2 % at 12).
 //
 // Issue order.  bf16: the fragments of the next K slice (32 x 32 blocks) or of the next group of
 // 16 MFMAs (16 x 16 blocks) are read into a second set of fragment registers before the MFMAs of
 // the current one are issued, and scheduling group barriers spread those reads between the
 // MFMAs, so the matrix pipe never waits for LDS.  fp8 keeps one set.
 //
-// Pipeline.  The kernel is persistent (one workgroup per CU): the load that a tile's last K step
-// issues is the first K step of the workgroup's NEXT tile, so consecutive tiles chain without
-// draining the pipeline and the epilogue's stores overlap the next tile's loads.
+// Pipeline.  The kernel is persistent (one workgroup per CU): the loads that a tile's last K
+// steps issue are the first K steps of the workgroup's NEXT tile, so consecutive tiles chain
+// without draining the pipeline and the epilogue's stores overlap the next tile's loads.  A
+// tile's 16-byte launch-order record is fetched two tiles ahead and moved to scalar registers
+// behind a K step's wait, its perm entries one tile ahead: nothing at a tile's start waits for
+// memory.
 //
 // Launch order.  Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b % 8).
 // The launch-order list (see tiles.hip) walks an expert's output in blocks of 8 x 4 tiles; it is

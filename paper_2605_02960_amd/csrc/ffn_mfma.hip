@@ -17,23 +17,22 @@
 // adjacent output columns and the lanes of one block row store whole 128-byte lines.
 //
 // fp8 (e4m3 codes, float scales per token row and per output channel): the accumulators hold sums
-// of code products and the scales are applied in the epilogue.
+// of code products and the scales are applied in the epilogue (the row scales travel in
+// registers, lane j of a wave holding the scale of the wave's row j).
 //
 // LDS.  A tile is [256 rows][128 bytes] in 8 chunks of 16 bytes per row; chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which makes the 16-byte fragment reads of the MFMA
-// operands free of bank conflicts.  One barrier per K step.  fp8: two stages of (token tile,
-// weight tile), 2 x 64 KB, plus the row scales.  bf16: five slots of 32 KB, all of the CU's 160 KB:
-// three for token tiles and two for weight tiles.
+// operands free of bank conflicts.  Five slots of 32 KB, all of the CU's 160 KB: three for token
+// tiles and two for weight tiles; one barrier per K step.
 //
 // Loader.  The operand tiles go from global memory straight into LDS (global_load_lds_dwordx4:
 // 16 bytes per lane, full 128-byte lines per row, no staging registers and no LDS store
 // instructions).  The instruction writes lane l at LDS base + 16 l, so the swizzle is applied on
 // the global side (the lane that fills position c' of row r fetches chunk c' ^ ((r >> 1) & 7)).
-// Rows of x are gathered through the lane offsets.  fp8: both tiles of K step k+1 are requested
-// at the top of step k and awaited (vmcnt(0) + barrier) at its end.  bf16: the top of step k
-// requests the weight tile of step k+1 and then the token tile of step k+2; the step's end waits
-// for all but the four youngest requests (requests are served in issue order), so the token
-// tiles, whose rows are gathered from all over x, have two steps to arrive (+2.4 %).
+// Rows of x are gathered through the lane offsets.  The top of K step k requests the weight tile
+// of step k+1 and then the token tile of step k+2; the step's end waits for all but the four
+// youngest requests (requests are served in issue order), so the token tiles, whose rows are
+// gathered from all over x, have two steps to arrive (+2.4 % for bf16, +1.3 % for fp8).
 //
 // MFMA blocks.  bf16 kernels whose tiles have 16 or more K steps multiply 16 x 16 x 32 blocks
 // (v_mfma_f32_16x16x32_bf16: half the accumulator writes per flop of the 32 x 32 x 16 form, which
@@ -67,14 +66,8 @@ constexpr int BM = 256;        // rows per tile
 constexpr int BK = 64;         // bf16 per K step
 constexpr int ROW_BYTES = BK * 2;
 constexpr int TILE_BYTES = 256 * ROW_BYTES;         // 32 KB
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;         // tokens + weights
 constexpr int THREADS = 512;
-constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * 256 * 4;   // + two buffers of 256 row scales (fp8)
-// bf16: three token-tile slots and two weight-tile slots, all of the 160 KB (see the kernel)
-#ifndef MOE_RING
-#define MOE_RING 1
-#endif
-constexpr int LDS_BYTES_RING = 5 * TILE_BYTES;
+constexpr int LDS_BYTES = 5 * TILE_BYTES;           // three token-tile slots and two weight-tile slots: all of the CU's 160 KB
 #ifndef MOE_GROUP_ROWS
 #define MOE_GROUP_ROWS 8
 #define MOE_GROUP_COLS 4
@@ -226,7 +219,20 @@ __device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int ti
 // lanes with equal fq write one contiguous run of a row (128 bytes of bf16 act, 256 or 512 bytes
 // of f32 y) per store instruction.
 // fp8: the accumulators hold sums of code products; the float scales of the row and of the output
-// channel are applied here, in float32: value = acc * (s_row * s_channel).
+// channel are applied here, in float32: value = acc * (s_row * s_channel).  Lane j of a wave
+// brings the scale of the wave's row j; the epilogue fetches it across lanes.
+// the value that the lane with byte address src_lane4 = 4 * lane index holds (every lane of the
+// wave must be active)
+__device__ __forceinline__ float from_lane4(float v, int src_lane4) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane4, __float_as_int(v)));
+}
+// 16 * fq, opaque to the optimiser: the lane addresses built from it are then formed where they
+// are used (one add each) instead of being kept in registers across the K loop
+__device__ __forceinline__ int opaque_fq16(int fq) {
+    int x = fq << 4;
+    asm volatile("" : "+v"(x));
+    return x;
+}
 // max over the 4 lanes of a quad (DPP quad permutes: lane ^ 1, then lane ^ 2)
 __device__ __forceinline__ float quad_max(float v) {
     int x = __float_as_int(v);
@@ -243,9 +249,10 @@ __device__ __forceinline__ float quad_max(float v) {
 template <bool FP8, int y_mode, typename ACC, int NN, int NM>
 __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const MfmaArgs& a,
                                                    const TileCtx& t, int wm, int wn, int fr, int fq,
-                                                   const float* row_scale) {
+                                                   float my_scale) {
     constexpr int BE = 64 / NM, VLEN = BE * BE / 64;
     constexpr int NGRP = NN / 4;                 // column ranges of 4*BE columns, 4 adjacent columns per lane
+    const int fq16 = FP8 ? opaque_fq16(fq) : 0;
     const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
     if (nb >= a.N) return;                       // N is a multiple of 128: the whole wave is in or out
     float sg[NN];
@@ -259,7 +266,7 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
             const int lrow = wm * 64 + mi * BE + (v >> 2) * 8 + fq * 4 + (v & 3);   // row inside the tile
             const int m = t.row0 + lrow;
             const bool live = m < t.row_end;     // the same for all lanes that share a row
-            const float sr = FP8 ? row_scale[lrow] : 1.f;
+            const float sr = FP8 ? from_lane4(my_scale, ((mi * BE + (v >> 2) * 8 + (v & 3)) << 2) + fq16) : 1.f;
 #pragma unroll
             for (int grp = 0; grp < NGRP; ++grp) {
                 float r[4];
@@ -304,23 +311,24 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
 template <bool FP8, typename ACC, int NN, int NM>
 __device__ __forceinline__ void store_tile_down(ACC (&acc)[NN][NM], const MfmaArgs& a,
                                                 const TileCtx& t, int wm, int wn, int fr, int fq,
-                                                const float* row_scale) {
+                                                float my_scale) {
     // one copy of the unrolled epilogue per storage form, chosen once per tile
-    if (a.y_mode == Y_BLOCK16) store_tile_down_as<FP8, Y_BLOCK16>(acc, a, t, wm, wn, fr, fq, row_scale);
-    else if (a.y_mode == Y_BLOCK16_AS_F32) store_tile_down_as<FP8, Y_BLOCK16_AS_F32>(acc, a, t, wm, wn, fr, fq, row_scale);
-    else store_tile_down_as<FP8, Y_EXACT_F32>(acc, a, t, wm, wn, fr, fq, row_scale);
+    if (a.y_mode == Y_BLOCK16) store_tile_down_as<FP8, Y_BLOCK16>(acc, a, t, wm, wn, fr, fq, my_scale);
+    else if (a.y_mode == Y_BLOCK16_AS_F32) store_tile_down_as<FP8, Y_BLOCK16_AS_F32>(acc, a, t, wm, wn, fr, fq, my_scale);
+    else store_tile_down_as<FP8, Y_EXACT_F32>(acc, a, t, wm, wn, fr, fq, my_scale);
 }
 
 template <int MODE, bool FP8, typename ACC, int NN_, int NM_>
 __device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs& a,
                                            const TileCtx& t, int wm, int wn, int fr, int fq,
-                                           const float* row_scale) {
+                                           float my_scale) {
     if constexpr (MODE == MODE_DOWN) {
-        store_tile_down<FP8>(acc, a, t, wm, wn, fr, fq, row_scale);
+        store_tile_down<FP8>(acc, a, t, wm, wn, fr, fq, my_scale);
     } else {
         constexpr int NM = NM_, BE = 64 / NM, VLEN = BE * BE / 64;
         constexpr int NBG = 64 / BE;              // adjacent output columns per lane
         constexpr int NPER = NBG;                                     // adjacent columns per lane
+        const int fq16 = FP8 ? opaque_fq16(fq) : 0;
         const int n = t.n0 + wn * 64 + NBG * fr;
         if (n >= a.N) return;
         float sg[NPER], su[NPER];   // per-channel scales (fp8): gate or down, and up
@@ -335,8 +343,9 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs&
             for (int v = 0; v < VLEN; ++v) {
                 const int lrow = wm * 64 + mi * BE + (v >> 2) * 8 + fq * 4 + (v & 3);   // row inside the tile
                 const int m = t.row0 + lrow;
+                // lane j of the wave holds the scale of the wave's row j (all lanes take part)
+                const float sr = FP8 ? from_lane4(my_scale, ((mi * BE + (v >> 2) * 8 + (v & 3)) << 2) + fq16) : 1.f;
                 if (m >= t.row_end) continue;
-                const float sr = FP8 ? row_scale[lrow] : 1.f;   // staged in LDS at the start of the tile
                 {
                     float h[NPER];
 #pragma unroll
@@ -371,9 +380,9 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
 }
 
 // 32 bytes of one LDS row (two swizzled 16-byte chunks) as one fp8 MFMA operand
-__device__ __forceinline__ i32x8 load_frag8(const char* row, uint32_t off0, uint32_t off1) {
-    const u32x4 lo = *reinterpret_cast<const u32x4*>(row + off0);
-    const u32x4 hi = *reinterpret_cast<const u32x4*>(row + off1);
+__device__ __forceinline__ i32x8 load_frag8(const char* p0, const char* p1) {
+    const u32x4 lo = *reinterpret_cast<const u32x4*>(p0);
+    const u32x4 hi = *reinterpret_cast<const u32x4*>(p1);
     return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
 }
 
@@ -428,7 +437,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         else frag_off[c] = (uint32_t)((((c % (8 / NG)) * NG + fq) ^ sw) << 4);               // c = kk
     }
     const uint32_t xa_row = (wm * 64 + fr) * ROW_BYTES;                    // + mi*BE rows
-    const uint32_t wb_base = TILE_BYTES + ((MODE == MODE_GATE_UP ? wn * 64 : wn * 128) + fr) * ROW_BYTES;
+    const uint32_t wb_row = ((MODE == MODE_GATE_UP ? wn * 64 : wn * 128) + fr) * ROW_BYTES;
     // block nj of the wave: gate/up: blocks 0..NN/2-1 are gate rows, the rest the matching up rows
     auto wb_off = [](int nj) -> uint32_t {
         if (MODE == MODE_GATE_UP) return (uint32_t)(((nj / (NN / 2)) * 128 + (nj % (NN / 2)) * BE) * ROW_BYTES);
@@ -438,53 +447,37 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     typedef typename std::conditional<BE == 32, f32x16, f32x4>::type acc_t;
     acc_t acc[NN][NM];
 
-    // ---- LDS slots.  fp8: two stages of (token tile, weight tile).  bf16 (RING): three token-tile
-    // slots [0, 3) and two weight-tile slots [3, 5) of 32 KB: the token tile of K step k+2 and the
-    // weight tile of step k+1 are requested at the top of step k (weights first), and the step's
-    // end waits for all but the last four requests, i.e. for the weight tile of step k+1 (the
-    // token tile of step k+1 is a step older).  Requests are served in issue order.
-    constexpr bool RING = !FP8 && MOE_RING != 0;
+    // ---- LDS slots: three token-tile slots [0, 3) and two weight-tile slots [3, 5) of 32 KB.  The
+    // token tile of K step k+2 and the weight tile of step k+1 are requested at the top of step k
+    // (weights first), and the step's end waits for all but the last four requests, i.e. for the
+    // weight tile of step k+1 (the token tile of step k+1 is a step older).  Requests are served
+    // in issue order.
     constexpr int NKK = FP8 ? 4 : 8 / NG;       // distinct fragment offsets per K step
-    uint32_t ad_a[NKK], ad_b[NKK];              // RING: byte offsets in LDS of the lane's fragments in the slots being read
-    int a_rd = 0, b_rd = 0;                     // RING: slots that hold the current K step
-    if constexpr (RING) {
+    uint32_t ad_a[NKK], ad_b[NKK];              // byte offsets in LDS of the lane's fragments in the slots being read
+    int a_rd = 0, b_rd = 0;                     // slots that hold the current K step
 #pragma unroll
-        for (int c = 0; c < NKK; ++c) {
-            ad_a[c] = xa_row + frag_off[c];
-            ad_b[c] = 3 * TILE_BYTES + (wb_base - TILE_BYTES) + frag_off[c];
-        }
+    for (int c = 0; c < NKK; ++c) {
+        ad_a[c] = xa_row + frag_off[c];
+        ad_b[c] = 3 * TILE_BYTES + wb_row + frag_off[c];
     }
-#define MOE_A_PTR(STAGE_, KK_) (RING ? smem + ad_a[KK_] : smem + (STAGE_) * STAGE_BYTES + xa_row + frag_off[KK_])
-#define MOE_B_PTR(STAGE_, KK_) (RING ? smem + ad_b[KK_] : smem + (STAGE_) * STAGE_BYTES + wb_base + frag_off[KK_])
+#define MOE_A_PTR(KK_) (smem + ad_a[KK_])
+#define MOE_B_PTR(KK_) (smem + ad_b[KK_])
 
-#define MOE_LOAD_FRAG8(PTR_, KK_) load_frag8((PTR_), frag_off[(KK_) * 2], frag_off[(KK_) * 2 + 1])
-#define MOE_COMPUTE(STAGE_)                                                               \
+    // fp8: a fragment is 32 bytes of a row = two swizzled 16-byte chunks
+#define MOE_COMPUTE_FP8()                                                                 \
     {                                                                                     \
-        const char* st = smem + (STAGE_) * STAGE_BYTES;                                   \
-        if constexpr (!FP8) {                                                             \
-            _Pragma("unroll") for (int kk = 0; kk < 8 / NG; ++kk) {                       \
-                bf16x8 xa[NM];                                                            \
-                _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) xa[mi] =                \
-                    *reinterpret_cast<const bf16x8*>(st + xa_row + mi * BE * ROW_BYTES + frag_off[kk]); \
-                _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) {                       \
-                    const bf16x8 wb =                                                     \
-                        *reinterpret_cast<const bf16x8*>(st + wb_base + wb_off(nj) + frag_off[kk]); \
-                    _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) acc[nj][mi] =       \
-                        mfma_bf16(xa[mi], wb, acc[nj][mi]);                               \
-                }                                                                         \
-            }                                                                             \
-        } else {                                                                          \
-            _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                            \
-                i32x8 xa[NM];                                                             \
-                _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                         \
-                    xa[mi] = MOE_LOAD_FRAG8(st + xa_row + mi * BE * ROW_BYTES, kk);       \
-                /* zero scale operands select the unscaled v_mfma_f32_32x32x64_f8f6f4 */   \
-                _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) {                       \
-                    const i32x8 wb = MOE_LOAD_FRAG8(st + wb_base + wb_off(nj), kk);       \
-                    _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) acc[nj][mi] =       \
-                        __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                  \
-                            xa[mi], wb, acc[nj][mi], 0, 0, 0, 0, 0, 0);                   \
-                }                                                                         \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                \
+            i32x8 xa[NM];                                                                 \
+            _Pragma("unroll") for (int mi = 0; mi < NM; ++mi)                             \
+                xa[mi] = load_frag8(MOE_A_PTR(kk * 2) + mi * BE * ROW_BYTES,              \
+                                    MOE_A_PTR(kk * 2 + 1) + mi * BE * ROW_BYTES);         \
+            /* zero scale operands select the unscaled v_mfma_f32_32x32x64_f8f6f4 */       \
+            _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) {                           \
+                const i32x8 wb = load_frag8(MOE_B_PTR(kk * 2) + wb_off(nj),               \
+                                            MOE_B_PTR(kk * 2 + 1) + wb_off(nj));          \
+                _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) acc[nj][mi] =           \
+                    __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                      \
+                        xa[mi], wb, acc[nj][mi], 0, 0, 0, 0, 0, 0);                       \
             }                                                                             \
         }                                                                                 \
     }
@@ -496,20 +489,6 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t dma_row0 = (uint32_t)(wave_u * 32) * ROW_BYTES;
-#define MOE_DMA_ISSUE(STAGE_, CTX_, KT_)                                                  \
-    {                                                                                     \
-        const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                  \
-        const char* abase = uniform_ptr(                                                  \
-            (MODE == MODE_GATE_UP) ? a.A : a.A + (size_t)CTX_.row0 * a.lda_bytes);        \
-        const char* bbase =                                                               \
-            uniform_ptr((MODE == MODE_DOWN || wave_u < 4) ? CTX_.b0e : CTX_.b1e);         \
-        const uint32_t st = __builtin_amdgcn_readfirstlane(                               \
-            lds_base + (STAGE_) * STAGE_BYTES + dma_row0);                                \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                     \
-            dma16(st + i * 8 * ROW_BYTES, CTX_.a_off[i] + kb, abase);                     \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                     \
-            dma16(st + TILE_BYTES + i * 8 * ROW_BYTES, CTX_.b_off[i] + kb, bbase);        \
-    }
     // Issue order inside one K step, imposed on the compiler's scheduler (which otherwise gathers
     // the LDS reads in blocks of their own): the loads come first (program order), then the
     // fragments of the first K slice; after that, 32x32 blocks: every MFMA followed by one fragment
@@ -541,12 +520,12 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // the MFMAs of slice k are issued; the staging registers that the direct-to-LDS loader no
     // longer needs pay for the second set
     bf16x8 fa0[NM], fb0[NN], fa1[NM], fb1[NN];
-#define MOE_FREAD(BUF_, STAGE_, KK_)                                                       \
+#define MOE_FREAD(BUF_, KK_)                                                               \
     {                                                                                      \
         _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) fa##BUF_[mi] =                   \
-            *reinterpret_cast<const bf16x8*>(MOE_A_PTR(STAGE_, KK_) + mi * BE * ROW_BYTES); \
+            *reinterpret_cast<const bf16x8*>(MOE_A_PTR(KK_) + mi * BE * ROW_BYTES); \
         _Pragma("unroll") for (int nj = 0; nj < NN; ++nj) fb##BUF_[nj] =                   \
-            *reinterpret_cast<const bf16x8*>(MOE_B_PTR(STAGE_, KK_) + wb_off(nj));         \
+            *reinterpret_cast<const bf16x8*>(MOE_B_PTR(KK_) + wb_off(nj));         \
     }
 #define MOE_FMFMA(BUF_)                                                                    \
     {                                                                                      \
@@ -564,15 +543,15 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // 16x16x32 blocks: a K step is two slices; a slice's weight fragments are handled in two
     // halves (blocks 0..NN/2-1 and the rest) so that two half buffers and two token-fragment
     // buffers suffice to keep the reads one group of 16 MFMAs ahead
-#define MOE_FREAD_A16(DST_, STAGE_, KK_)                                                   \
+#define MOE_FREAD_A16(DST_, KK_)                                                           \
     {                                                                                      \
         _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) DST_[mi] =                       \
-            *reinterpret_cast<const bf16x8*>(MOE_A_PTR(STAGE_, KK_) + mi * BE * ROW_BYTES); \
+            *reinterpret_cast<const bf16x8*>(MOE_A_PTR(KK_) + mi * BE * ROW_BYTES); \
     }
-#define MOE_FREAD_B16(HALF_, STAGE_, KK_)                                                  \
+#define MOE_FREAD_B16(HALF_, KK_)                                                          \
     {                                                                                      \
         _Pragma("unroll") for (int q = 0; q < NN / 2; ++q) fb0[(HALF_) * (NN / 2) + q] =   \
-            *reinterpret_cast<const bf16x8*>(MOE_B_PTR(STAGE_, KK_) + wb_off((HALF_) * (NN / 2) + q)); \
+            *reinterpret_cast<const bf16x8*>(MOE_B_PTR(KK_) + wb_off((HALF_) * (NN / 2) + q)); \
     }
 #define MOE_FMFMA16(FA_, HALF_, Z_)                                                        \
     {                                                                                      \
@@ -583,25 +562,25 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                 else acc[njh + q][mi] = mfma_bf16(FA_[mi], fb0[njh + q], acc[njh + q][mi]); \
             }                                                                              \
     }
-#define MOE_COMPUTE_STEP(STAGE_, FIRST_)                                                   \
+#define MOE_COMPUTE_STEP(FIRST_)                                                           \
     if constexpr (!FP8 && BE == 32) {                                                      \
-        MOE_FREAD(0, STAGE_, 0);                                                           \
-        MOE_FREAD(1, STAGE_, 1);                                                           \
+        MOE_FREAD(0, 0);                                                                   \
+        MOE_FREAD(1, 1);                                                                   \
         if constexpr (FIRST_) MOE_FMFMA_Z(0) else MOE_FMFMA(0);                            \
-        MOE_FREAD(0, STAGE_, 2);                                                           \
+        MOE_FREAD(0, 2);                                                                   \
         MOE_FMFMA(1);                                                                      \
-        MOE_FREAD(1, STAGE_, 3);                                                           \
+        MOE_FREAD(1, 3);                                                                   \
         MOE_FMFMA(0);                                                                      \
         MOE_FMFMA(1);                                                                      \
     } else if constexpr (!FP8 && BE == 16) {                                               \
-        MOE_FREAD_A16(fa0, STAGE_, 0);                                                     \
-        MOE_FREAD_B16(0, STAGE_, 0);                                                       \
-        MOE_FREAD_B16(1, STAGE_, 0);                                                       \
+        MOE_FREAD_A16(fa0, 0);                                                             \
+        MOE_FREAD_B16(0, 0);                                                               \
+        MOE_FREAD_B16(1, 0);                                                               \
         MOE_FMFMA16(fa0, 0, FIRST_);                                                       \
-        MOE_FREAD_A16(fa1, STAGE_, 1);                                                     \
-        MOE_FREAD_B16(0, STAGE_, 1);                                                       \
+        MOE_FREAD_A16(fa1, 1);                                                             \
+        MOE_FREAD_B16(0, 1);                                                               \
         MOE_FMFMA16(fa0, 1, FIRST_);                                                       \
-        MOE_FREAD_B16(1, STAGE_, 1);                                                       \
+        MOE_FREAD_B16(1, 1);                                                               \
         MOE_FMFMA16(fa1, 0, false);                                                        \
         MOE_FMFMA16(fa1, 1, false);                                                        \
     } else {                                                                               \
@@ -611,19 +590,9 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                     _Pragma("unroll") for (int v = 0; v < Blk<FP8, BLK>::VLEN; ++v)              \
                         acc[nj][mi][v] = 0.f;                                              \
         }                                                                                  \
-        MOE_COMPUTE(STAGE_);                                                               \
+        MOE_COMPUTE_FP8();                                                                 \
     }
-    // one K step: multiply LDS stage S_ while step KT_ of CTX_ lands in the other stage
-#define MOE_STEP(S_, CTX_, KT_, FIRST_)                                                    \
-    {                                                                                      \
-        MOE_DMA_ISSUE(1 - (S_), CTX_, KT_);                                                \
-        MOE_COMPUTE_STEP(S_, FIRST_);                                                      \
-        MOE_ISSUE_ORDER();                                                                 \
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                   \
-        __syncthreads();                                                                   \
-    }
-
-    // RING: one operand tile of K step KT_ of CTX_ into slot SLOT_ (4 requests per wave)
+    // one operand tile of K step KT_ of CTX_ into slot SLOT_ (4 requests per wave)
 #define MOE_DMA_A(SLOT_, CTX_, KT_)                                                        \
     {                                                                                      \
         const uint32_t kb = (uint32_t)(KT_) * ROW_BYTES;                                   \
@@ -644,14 +613,14 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
             dma16(st + i * 8 * ROW_BYTES, CTX_.b_off[i] + kb, bbase);                      \
     }
-    // RING, one K step: request the weight tile of step KTB_ of CB_ (the next step) and the token
+    // One K step: request the weight tile of step KTB_ of CB_ (the next step) and the token
     // tile of step KTA_ of CA_ (the step after), multiply the current slots, wait for everything
     // but the token tile just requested, move on to the next slots
-#define MOE_RSTEP(CB_, KTB_, CA_, KTA_, FIRST_)                                            \
+#define MOE_STEP(CB_, KTB_, CA_, KTA_, FIRST_)                                            \
     {                                                                                      \
         MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                                                    \
         MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
-        MOE_COMPUTE_STEP(0, FIRST_);                                                       \
+        MOE_COMPUTE_STEP(FIRST_);                                                          \
         MOE_ISSUE_ORDER();                                                                 \
         asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
         __syncthreads();                                                                   \
@@ -675,81 +644,59 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // registers right behind a K step's own wait: nothing at a tile's start waits for memory (a
     // wait there would also wait for the previous tile's stores).
     int4 rec_v = a.order[min(L + stride, total - 1)];
-    if constexpr (RING) {
-        MOE_DMA_A(0, cur, 0);
-        MOE_DMA_B(0, cur, 0);
-        MOE_DMA_A(1, cur, 1);
-    } else {
-        MOE_DMA_ISSUE(0, cur, 0);
-    }
+    MOE_DMA_A(0, cur, 0);
+    MOE_DMA_B(0, cur, 0);
+    MOE_DMA_A(1, cur, 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int4 rec_s = uniform_rec(rec_v);
     __syncthreads();
 
-    int tile_parity = 0;
-    // Invariant at the top of every tile: LDS stage 0 holds its K step 0; rec_s is the next tile's record.
+    // Invariant at the top of every tile: token slot a_rd holds its K step 0, the next token slot
+    // its step 1, weight slot b_rd its step 0; rec_s is the next tile's record.
     for (;;) {
         L += stride;
         const bool has_next = L < l_end;
         if (has_next) ctx_from_rec<MODE>(nxt, a, rec_s, tid);
-        else nxt = cur;   // nothing follows: the trailing load re-reads this tile (harmless)
+        else nxt = cur;   // nothing follows: the trailing loads re-read this tile (harmless)
         rec_v = a.order[min(L + stride, total - 1)];
-        float* row_scale = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES) + (tile_parity << 8);
-        if (FP8 && tid < BM) row_scale[tid] = a.sA[min(cur.row0 + tid, cur.row_end - 1)];
-        tile_parity ^= 1;   // the buffer is read in this tile's epilogue, many barriers from here
+        // fp8: lane j of a wave brings the scale of the wave's row j for the epilogue
+        float my_scale = 1.f;
+        if (FP8) my_scale = a.sA[min(cur.row0 + wm * 64 + lane, cur.row_end - 1)];
 
-        if constexpr (RING) {
-            // Invariant at the top of K step k: token slot a_rd holds step k, the next token slot
-            // holds (or is receiving) step k+1, weight slot b_rd holds step k.
-            if (KT > 2) {
-                MOE_RSTEP(cur, 1, cur, 2, true);
-                rec_s = uniform_rec(rec_v);
-                for (int kt = 1; kt < KT - 2; ++kt) MOE_RSTEP(cur, kt + 1, cur, kt + 2, false);
-                if (has_next) {
-                    fill_a_off<MODE>(nxt, a, tid);
-                    fill_b_off<MODE, BE>(nxt, a, tid);
-                }
-                // last two steps of this tile: their requests reach into the next tile
-                MOE_RSTEP(cur, KT - 1, nxt, 0, false);
-                MOE_RSTEP(nxt, 0, nxt, 1, false);
-            } else {
-                if (has_next) {
-                    fill_a_off<MODE>(nxt, a, tid);
-                    fill_b_off<MODE, BE>(nxt, a, tid);
-                }
-                MOE_RSTEP(cur, 1, nxt, 0, true);
-                rec_s = uniform_rec(rec_v);
-                MOE_RSTEP(nxt, 0, nxt, 1, false);
-            }
-        } else {
-            MOE_STEP(0, cur, 1, true);
+        // Invariant at the top of K step k: token slot a_rd holds step k, the next token slot
+        // holds (or is receiving) step k+1, weight slot b_rd holds step k.
+        if (KT > 2) {
+            MOE_STEP(cur, 1, cur, 2, true);
             rec_s = uniform_rec(rec_v);
-            for (int kt = 1; kt < KT - 1; kt += 2) {
-                MOE_STEP(1, cur, kt + 1, false);
-                MOE_STEP(0, cur, kt + 2, false);
-            }
-            // last step of this tile: its load is step 0 of the next tile
+            for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP(cur, kt + 1, cur, kt + 2, false);
             if (has_next) {
                 fill_a_off<MODE>(nxt, a, tid);
                 fill_b_off<MODE, BE>(nxt, a, tid);
             }
-            MOE_STEP(1, nxt, 0, false);
+            // last two steps of this tile: their requests reach into the next tile
+            MOE_STEP(cur, KT - 1, nxt, 0, false);
+            MOE_STEP(nxt, 0, nxt, 1, false);
+        } else {
+            if (has_next) {
+                fill_a_off<MODE>(nxt, a, tid);
+                fill_b_off<MODE, BE>(nxt, a, tid);
+            }
+            MOE_STEP(cur, 1, nxt, 0, true);
+            rec_s = uniform_rec(rec_v);
+            MOE_STEP(nxt, 0, nxt, 1, false);
         }
 
-        store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fq, row_scale);
+        store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fq, my_scale);
         if (!has_next) {
             // the last step's token-tile requests are still on their way into this workgroup's LDS
-            if constexpr (RING) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             break;
         }
         cur = nxt;
     }
-#undef MOE_COMPUTE
-#undef MOE_LOAD_FRAG8
+#undef MOE_COMPUTE_FP8
 #undef MOE_ISSUE_ORDER
-#undef MOE_DMA_ISSUE
 #undef MOE_STEP
-#undef MOE_RSTEP
 #undef MOE_DMA_A
 #undef MOE_DMA_B
 #undef MOE_A_PTR
@@ -803,18 +750,16 @@ inline bool use_blk16(int kt) { return kt >= 16; }
 
 template <int MODE>
 int32_t launch_kernel(bool fp8, const MfmaArgs& args, dim3 grid, hipStream_t s) {
-    constexpr int LDS_BF16 = MOE_RING != 0 ? LDS_BYTES_RING : LDS_BYTES;
     if (fp8) ffn_mfma_kernel<MODE, true, 32><<<grid, THREADS, LDS_BYTES, s>>>(args);
-    else if (use_blk16(args.KT)) ffn_mfma_kernel<MODE, false, 16><<<grid, THREADS, LDS_BF16, s>>>(args);
-    else ffn_mfma_kernel<MODE, false, 32><<<grid, THREADS, LDS_BF16, s>>>(args);
+    else if (use_blk16(args.KT)) ffn_mfma_kernel<MODE, false, 16><<<grid, THREADS, LDS_BYTES, s>>>(args);
+    else ffn_mfma_kernel<MODE, false, 32><<<grid, THREADS, LDS_BYTES, s>>>(args);
     return launch_status();
 }
 
 template <int MODE, bool FP8, int BLK>
 bool allow_lds() {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_mfma_kernel<MODE, FP8, BLK>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (!FP8 && MOE_RING != 0) ? LDS_BYTES_RING : LDS_BYTES) == hipSuccess;
+                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess;
 }
 template <bool FP8>
 int32_t set_kernel_attributes() {

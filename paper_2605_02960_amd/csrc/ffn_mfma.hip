@@ -259,14 +259,24 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
 #pragma unroll
     for (int j = 0; j < NN; ++j)
         sg[j] = FP8 ? a.sB0[(size_t)t.e * a.N + nb + (j >> 2) * (4 * BE) + 4 * fr + (j & 3)] : 1.f;
+    // Addresses: a scalar base per row of the wave (wm, wn, the tile and the loop indices are all
+    // wave-uniform) plus one 32-bit lane offset, so that a store needs no vector address arithmetic.
+    constexpr uint32_t ESZ = (y_mode == Y_BLOCK16) ? 2 : 4;              // bytes per stored element
+    const uint32_t row_bytes = (uint32_t)a.N * ESZ;
+    char* const wave_base = a.C + ((size_t)(t.row0 + wm * 64) * a.N + nb) * ESZ;
+    const uint32_t lane_off = (uint32_t)(fq * 4) * row_bytes + (uint32_t)(4 * fr) * ESZ;
+    const uint32_t erow_bytes = (uint32_t)a.N / Y_BLOCK;                 // exponent bytes per row
+    uint8_t* const wave_ebase = (y_mode == Y_BLOCK16) ? a.Cs + (size_t)(t.row0 + wm * 64) * erow_bytes + nb / Y_BLOCK : nullptr;
+    const uint32_t lane_eoff = (uint32_t)(fq * 4) * erow_bytes + (uint32_t)(fr >> 2);
+    const int rows_left = t.row_end - t.row0 - wm * 64 - fq * 4;         // rows of the group from this lane's first row on
 #pragma unroll
     for (int mi = 0; mi < NM; ++mi) {
 #pragma unroll
         for (int v = 0; v < VLEN; ++v) {
-            const int lrow = wm * 64 + mi * BE + (v >> 2) * 8 + fq * 4 + (v & 3);   // row inside the tile
-            const int m = t.row0 + lrow;
-            const bool live = m < t.row_end;     // the same for all lanes that share a row
-            const float sr = FP8 ? from_lane4(my_scale, ((mi * BE + (v >> 2) * 8 + (v & 3)) << 2) + fq16) : 1.f;
+            const int rc = mi * BE + (v >> 2) * 8 + (v & 3);             // row of the wave, less the lane's 4 * fq
+            const bool live = rc < rows_left;    // the same for all lanes that share a row
+            const float sr = FP8 ? from_lane4(my_scale, (rc << 2) + fq16) : 1.f;
+            char* const row_base = wave_base + (size_t)rc * row_bytes;
 #pragma unroll
             for (int grp = 0; grp < NGRP; ++grp) {
                 float r[4];
@@ -275,12 +285,12 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
                     r[q] = acc[grp * 4 + q][mi][v];
                     if (FP8) r[q] *= sr * sg[grp * 4 + q];
                 }
-                const int n = nb + grp * (4 * BE) + 4 * fr;
+                char* const dst = row_base + grp * (4 * BE) * ESZ + lane_off;
                 if (y_mode == Y_EXACT_F32) {
                     if (!live) continue;
                     f32x4 o = {r[0], r[1], r[2], r[3]};
                     // y is read back (by the combine) only after gigabytes more have gone by: streaming store
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n));
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
                     continue;
                 }
                 const float amax = quad_max(fmaxf(fmaxf(fabsf(r[0]), fabsf(r[1])), fmaxf(fabsf(r[2]), fabsf(r[3]))));
@@ -296,12 +306,13 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
                     f32x4 o;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) o[q] = sc * (float)(int)(short)(c[q] & 0xFFFFu);
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.C) + (size_t)m * a.N + n));
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
                 } else {
                     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
                     u32x2 o = {(c[0] & 0xFFFFu) | (c[1] << 16), (c[2] & 0xFFFFu) | (c[3] << 16)};
-                    __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(reinterpret_cast<int16_t*>(a.C) + (size_t)m * a.N + n));
-                    if ((fr & 3) == 0) a.Cs[(size_t)m * (a.N / Y_BLOCK) + n / Y_BLOCK] = (uint8_t)(kf >> 23);
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(dst));
+                    if ((fr & 3) == 0)
+                        (wave_ebase + (size_t)rc * erow_bytes + grp * (4 * BE / Y_BLOCK))[lane_eoff] = (uint8_t)(kf >> 23);
                 }
             }
         }
@@ -337,15 +348,19 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs&
             sg[q] = FP8 ? a.sB0[(size_t)t.e * a.N + n + q] : 1.f;
             su[q] = FP8 ? a.sB1[(size_t)t.e * a.N + n + q] : 1.f;
         }
+        // addresses: scalar base per row of the wave + one 32-bit lane offset (see the down epilogue)
+        const uint32_t row_bytes = (uint32_t)a.N * 2;
+        char* const wave_base = a.C + ((size_t)(t.row0 + wm * 64) * a.N + t.n0 + wn * 64) * 2;
+        const uint32_t lane_off = (uint32_t)(fq * 4) * row_bytes + (uint32_t)(NBG * fr) * 2;
+        const int rows_left = t.row_end - t.row0 - wm * 64 - fq * 4;
 #pragma unroll
         for (int mi = 0; mi < NM; ++mi) {
 #pragma unroll
             for (int v = 0; v < VLEN; ++v) {
-                const int lrow = wm * 64 + mi * BE + (v >> 2) * 8 + fq * 4 + (v & 3);   // row inside the tile
-                const int m = t.row0 + lrow;
+                const int rc = mi * BE + (v >> 2) * 8 + (v & 3);         // row of the wave, less the lane's 4 * fq
                 // lane j of the wave holds the scale of the wave's row j (all lanes take part)
-                const float sr = FP8 ? from_lane4(my_scale, ((mi * BE + (v >> 2) * 8 + (v & 3)) << 2) + fq16) : 1.f;
-                if (m >= t.row_end) continue;
+                const float sr = FP8 ? from_lane4(my_scale, (rc << 2) + fq16) : 1.f;
+                if (rc >= rows_left) continue;
                 {
                     float h[NPER];
 #pragma unroll
@@ -357,7 +372,7 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs&
                         }
                         h[q] = silu_mul(g, u);
                     }
-                    uint16_t* dst = reinterpret_cast<uint16_t*>(a.C) + (size_t)m * a.N + n;
+                    char* const dst = wave_base + (size_t)rc * row_bytes + lane_off;
                     if (NPER == 2) {
                         *reinterpret_cast<uint32_t*>(dst) = pack2_bf16(h[0], h[1]);
                     } else {
@@ -686,7 +701,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             MOE_STEP(nxt, 0, nxt, 1, false);
         }
 
-        store_tile<MODE, FP8>(acc, a, cur, wm, wn, fr, fq, my_scale);
+        store_tile<MODE, FP8>(acc, a, cur, wave_u & 3, wave_u >> 2, fr, fq, my_scale);
         if (!has_next) {
             // the last step's token-tile requests are still on their way into this workgroup's LDS
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -100,7 +100,7 @@ struct MfmaArgs {
     const int4* order;      // launch slot -> (expert, first row, end row, column tile)
     char* C;                // act [P,I] bf16, or y [P,H]: float32 (y_mode 0, 1) or int16 codes (y_mode 2)
     uint8_t* Cs;            // y_mode 2: block exponents [P][N/16]
-    int32_t y_mode;         // down only, see Y_* below
+    int32_t y_mode;         // down only, see Y_* above
     int32_t nct;            // column tiles
 };
 

@@ -233,12 +233,21 @@ __device__ __forceinline__ int opaque_fq16(int fq) {
     asm volatile("" : "+v"(x));
     return x;
 }
-// max over the 4 lanes of a quad (DPP quad permutes: lane ^ 1, then lane ^ 2)
-__device__ __forceinline__ float quad_max(float v) {
-    int x = __float_as_int(v);
-    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false)));
-    x = __float_as_int(v);
-    return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false)));
+// Largest magnitude of the 16 values that the 4 lanes of a quad hold (4 each): absolute values as
+// source modifiers, then the maximum with lane ^ 1 and with lane ^ 2 as DPP operands of the max
+// itself (two wait states between writing a register and reading it through DPP).  Every lane of
+// the quad must be active.
+__device__ __forceinline__ float quad_amax4(float a, float b, float c, float d) {
+    float m;
+    asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\t"
+        "v_max_f32 %0, %0, |%4|\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+        : "=&v"(m)
+        : "v"(a), "v"(b), "v"(c), "v"(d));
+    return m;
 }
 
 // Down projection epilogue.  A lane holds 4 adjacent columns of a row per column range, the 4
@@ -293,7 +302,7 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
                     __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
                     continue;
                 }
-                const float amax = quad_max(fmaxf(fmaxf(fabsf(r[0]), fabsf(r[1])), fmaxf(fabsf(r[2]), fabsf(r[3]))));
+                const float amax = quad_amax4(r[0], r[1], r[2], r[3]);
                 uint32_t kf = (__float_as_uint(amax) + 0x100u) & 0x7F800000u;   // k << 23
                 kf = max(kf, 15u << 23);
                 const float inv = __uint_as_float((268u << 23) - kf);           // 2^(141-k)
@@ -309,7 +318,8 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
                     __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
                 } else {
                     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-                    u32x2 o = {(c[0] & 0xFFFFu) | (c[1] << 16), (c[2] & 0xFFFFu) | (c[3] << 16)};
+                    // low halves of two registers side by side (v_perm_b32: bytes 0-3 from the second source, 4-7 from the first)
+                    u32x2 o = {__builtin_amdgcn_perm(c[1], c[0], 0x05040100u), __builtin_amdgcn_perm(c[3], c[2], 0x05040100u)};
                     __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(dst));
                     if ((fr & 3) == 0)
                         (wave_ebase + (size_t)rc * erow_bytes + grp * (4 * BE / Y_BLOCK))[lane_eoff] = (uint8_t)(kf >> 23);

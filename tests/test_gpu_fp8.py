@@ -144,6 +144,19 @@ def test_fp8_qwen3_layer_32k_tokens():
     assert torch.equal(out, r["out"])
 
 
+@pytest.mark.parametrize("T,H,E,K,I", [
+    (1, 256, 3, 3, 256),       # one token, every expert chosen
+    (130, 256, 1, 1, 512),     # one expert, a group that ends two rows into a 64-row block
+], ids=["one_token_k_eq_e", "one_expert"])
+def test_fp8_degenerate_shapes(T, H, E, K, I):
+    w = workloads.scaled(workloads.QWEN3_32K_FP8, name=f"fp8_degenerate_{T}_{H}_{E}_{K}_{I}", T=T, H=H, E=E, K=K, I=I)
+    cfg, g8, r = _fp8_case(w, None, gate_end_to_end=False)
+    out = moe.moe_prefill_layer(cfg, g8["x"], g8["w_router"], g8["bias"], g8["w_gate"], g8["w_up"], g8["w_down"],
+                                g8["s_gate"], g8["s_up"], g8["s_down"])
+    torch.cuda.synchronize()
+    assert torch.equal(out, r["out"])
+
+
 @pytest.mark.parametrize("seed", range(5))
 def test_fp8_random_small_shapes(seed):
     """Seeded random shapes of the fp8 path (H, I multiples of 256; any T, E, K; with and without

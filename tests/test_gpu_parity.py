@@ -375,6 +375,21 @@ def test_y_block16_storage_is_the_quantiser_applied_to_the_float32_result():
     assert gu.max_err_over_rms(r16["out"].cpu().numpy(), r32["out"].cpu().numpy()) <= 3e-4
 
 
+@pytest.mark.parametrize("T,H,E,K,I", [
+    (1, 128, 4, 4, 128),       # one token, every expert chosen (K = E): four groups of one row
+    (1, 256, 1, 1, 128),       # one token, one expert
+    (300, 128, 1, 1, 256),     # one expert takes everything: a single group of two row tiles
+    (65, 384, 7, 7, 128),      # K = E: every group has all T rows (one row past a 64-row block)
+], ids=["one_token_k_eq_e", "one_token_one_expert", "one_expert", "k_eq_e"])
+def test_bf16_degenerate_shapes(T, H, E, K, I):
+    """The smallest and the most lopsided cases the method has, every token checked."""
+    w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name=f"bf16_degenerate_{T}_{H}_{E}_{K}_{I}", T=T, H=H, E=E, K=K, I=I)
+    d, g, cfg, r, info = _layer_case(w)
+    assert int(r["counts"].sum()) == T * K
+    _bf16_checks(w, d, g, cfg, r, info, None)
+    assert torch.equal(_fused(cfg, g), r["out"])
+
+
 def _random_bf16_shape(seed):
     rng = np.random.default_rng(1000 + seed)
     H = 128 * int(rng.integers(1, 5))

@@ -60,12 +60,10 @@ def main():
     import workloads
 
     if a.sched:
-        if not os.path.exists(moe.lib_path()):
-            moe_build.build()
+        moe_build.ensure_built()
         return sched_mode(a, np, moe, workloads)
 
-    if not os.path.exists(moe.lib_path()):
-        moe_build.build()
+    moe_build.ensure_built()
     if a.sweep:
         return sweep(a, np, torch, moe, workloads)
     if a.stream:

@@ -6,8 +6,8 @@
  * the current MoE layer entirely on-device; Sec. 1: dispatch becomes a local
  * operation).  Sec. 2.3 defines the computation: E experts, each a two-layer MLP;
  * a router sends each token to its top-k experts and their outputs are summed.
- * The "auxiliary" token permutation/alignment steps that Sec. 4.3 places on the
- * critical path of every layer are moe_permute here.
+ * The token permutation/alignment steps that Sec. 4.3 counts among the small
+ * kernels on every layer's critical path are moe_permute here.
  *
  * Conventions (all entry points)
  *   - Every data pointer is DEVICE memory owned by the caller, on the device that
@@ -15,11 +15,20 @@
  *     nothing and keeps no pointer after the call's kernels have run.  Scratch
  *     space comes in through (ws, ws_bytes); its minimum size is
  *     moe_workspace_bytes(cfg, call).  ws must be 256-byte aligned.
+ *   - Host-side state: per device, the compute-unit count and a one-time kernel
+ *     attribute set-up, made under a mutex by the first call on that device (calls
+ *     from several host threads are safe); that first call queries the device and
+ *     must not fall inside a stream capture: call moe_init_device() once per device
+ *     beforehand if it would.  The event pairs of moe_set_profile_events are
+ *     process-global and not thread-safe.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work: no host synchronisation and no device-to-host copy.
  *   - Tensors are dense row-major; "[A,B]" lists dimensions slowest first.
  *   - Return value: MOE_OK (0) or a negative moe_status.  Argument errors are
  *     found on the host before anything is enqueued and leave outputs untouched.
+ *     MOE_ERR_LAUNCH_FAILED is read from hipGetLastError after each launch, so it
+ *     also reports (and clears) an error that an earlier HIP call of the calling
+ *     thread left pending.
  *   - Routed rows: P = T*K.  A routed row has a flat id f = t*K + j (token t,
  *     slot j) and a sorted position p in [0,P): rows are sorted by expert id,
  *     and by ascending flat id inside one expert's group.
@@ -66,6 +75,10 @@ enum { /* moe_config.flags */
      * kernels; an element moves by at most 2^(k-142) <= amax/32768 (measured 1e-4 * rms on the
      * layer output, against the 1e-2 * rms that rounding the activations to bf16 contributes).
      * The float32 y that moe_grouped_ffn writes and the y_perm tap hold exactly these values.
+     * Non-finite values do not survive this form as themselves: a block that contains +-Inf
+     * (an overflowed accumulator) gets exponent byte 255 and reads back as NaN in every one of
+     * its 16 elements (so the overflow stays visible in out); a NaN element, which only
+     * unsupported NaN input can produce, reads back as 0.
      * No effect on the F32 path. */
     MOE_FLAG_Y_F32 = 1
 };
@@ -130,6 +143,10 @@ typedef enum moe_kernel {
 int32_t moe_abi_version(void);
 const char *moe_status_string(int32_t status);
 
+/* One-time set-up for the device that is current: what the first compute call on a device would
+ * otherwise do itself (see "Host-side state" above).  Idempotent, thread-safe, allocates nothing. */
+int32_t moe_init_device(void);
+
 /* Minimum workspace, in bytes, of one entry point for this config. */
 int32_t moe_workspace_bytes(const moe_config_t *cfg, int32_t call, size_t *bytes_out);
 
@@ -150,8 +167,8 @@ int32_t moe_set_profile_events(int32_t kernel, void *start_event, void *stop_eve
 int32_t moe_quantize_rows_e4m3(const void *src_bf16, int64_t rows, int32_t cols, uint8_t *q,
                                float *scale, void *stream);
 
-/* Router (Sec. 2.3, "a lightweight router dispatches each token to its top-k
- * experts").  logits[t,e] = sum_h x[t,h]*w_router[e,h] (+ bias[e]), accumulated in
+/* Router (Sec. 2.3: every token is dispatched to its top-k experts by a small
+ * linear router).  logits[t,e] = sum_h x[t,h]*w_router[e,h] (+ bias[e]), accumulated in
  * float32; per token the K largest logits in descending order, equal values
  * ordered by ascending expert index; topk_w = softmax over the selected logits
  * (equal to the full softmax renormalised over the selection).
@@ -197,7 +214,7 @@ int32_t moe_grouped_ffn(const moe_config_t *cfg, const void *x, const int32_t *p
                         float *act_scale_tap, float *y_perm, void *ws, size_t ws_bytes,
                         void *stream);
 
-/* Weighted combine back to token order ("sums their outputs", Sec. 2.3):
+/* Weighted combine back to token order (the sum over a token's k expert outputs, Sec. 2.3):
  *   out[t,:] = sum_{j<K} topk_w[t,j] * y_perm[inv_perm[t*K+j],:], float32 FMA in
  *   slot order, one rounding to out_dtype.  out [T,H]. */
 int32_t moe_combine(const moe_config_t *cfg, const float *y_perm, const int32_t *inv_perm,
@@ -211,7 +228,7 @@ int32_t moe_prefill_layer(const moe_config_t *cfg, const void *x, const float *w
                           const float *s_down, void *out, const moe_taps_t *taps, void *ws,
                           size_t ws_bytes, void *stream);
 
-/* ---- One-GPU weight streaming (the "one-GPU H2D streaming" mode of the weight streaming engine,
+/* ---- One-GPU weight streaming (the single-GPU host-to-device mode of the weight streaming engine,
  * App. B.1; offloading pipeline of Sec. 6.3) and the saturation threshold (Eq. 1; App. B.4 Eq. 3).
  *
  * The expert weights of all layers stay in PINNED HOST memory; the GPU holds n_slots layer
@@ -255,6 +272,21 @@ double moe_saturation_threshold_flops(double t_ep_seconds, double f_gpu_flops, d
  * collapses to gamma * C_dummy when t_e <= t_c, which is also the fallback when t_c is not
  * positive (no calibration yet). */
 double moe_calibrated_threshold_flops(double t_c, double t_e, double c_dummy_flops, double gamma);
+
+/* App. B.4, delivery and fallback: the threshold the frontend installs, and the unit that both it
+ * and the work counters L_i are kept in.
+ *   pinned > 0          the operator's manual value is used as it is (a calibration result is
+ *                       skipped); its unit follows f_tok as below.
+ *   f_tok > 0           FLOPs: T = Eq. 3 with C_dummy = f_tok * n_ref (before any calibration,
+ *                       t_c <= 0, this is gamma * f_tok * n_ref).
+ *   f_tok not positive  (the model configuration lacks what f_tok needs) token-unit accounting:
+ *                       the same formula with one unit of work per token, T = gamma *
+ *                       max(t_e/t_c, 1) * n_ref tokens; the scheduling round is then run with
+ *                       f_tok = 1, f_attn = 0 so that L_i counts uncached tokens.
+ * Host arithmetic only.  gamma must be positive and n_ref non-negative (MOE_ERR_BAD_SHAPE). */
+enum { MOE_UNIT_FLOPS = 0, MOE_UNIT_TOKENS = 1 };
+int32_t moe_resolve_threshold(double pinned, double t_c, double t_e, double f_tok, double n_ref,
+                              double gamma, double *threshold_out, int32_t *unit_out);
 
 #ifdef __cplusplus
 }

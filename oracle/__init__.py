@@ -17,5 +17,7 @@ Parity pins (tests/test_oracle_*.py): brute-force loops, closed forms
 (softmax over the selected logits, dense SwiGLU for E=1,k=1), invariants
 (counts sum to T*k, bijective permutation, weights sum to 1, identical experts
 collapse to one expert), scaling laws, an enumerated e4m3 table and torch's CPU
-casts as an independent codec.  No function here is "parity unpinned".
+casts as an independent codec; down_project (the second expert GEMM on its own)
+against a hand-worked case, plain loops and the layer's own y.  No function here
+is "parity unpinned".
 """

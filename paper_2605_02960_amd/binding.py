@@ -8,7 +8,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmoeprefill.so")
+# MOE_PREFILL_LIB: another build of the same library to load instead (A/B timing of kernel variants)
+_LIB_PATH = os.environ.get("MOE_PREFILL_LIB") or os.path.join(_HERE, "libmoeprefill.so")
 _lib = None
 
 DTYPE_F32, DTYPE_BF16, DTYPE_FP8_E4M3 = 0, 1, 2
@@ -20,8 +21,8 @@ KERNEL_NAMES = ("router_gemm", "topk", "permute", "gate_up", "down", "combine")
 
 EXPORTED_SYMBOLS = (
     "moe_layer_weight_bytes", "moe_prefill_layers_streamed", "moe_layer_flops_per_token",
-    "moe_saturation_threshold_flops", "moe_calibrated_threshold_flops",
-    "moe_abi_version", "moe_status_string", "moe_set_profile_events", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
+    "moe_saturation_threshold_flops", "moe_calibrated_threshold_flops", "moe_resolve_threshold",
+    "moe_abi_version", "moe_status_string", "moe_init_device", "moe_set_profile_events", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
     "moe_sched_create", "moe_sched_destroy", "moe_sched_hash_blocks", "moe_sched_round",
     "moe_sched_blocks_stored", "moe_sched_blocks_evicted", "moe_sched_table_size",
@@ -73,6 +74,8 @@ def lib():
         L.moe_abi_version.argtypes = []
         L.moe_status_string.restype = ctypes.c_char_p
         L.moe_status_string.argtypes = [i32]
+        L.moe_init_device.restype = i32
+        L.moe_init_device.argtypes = []
         L.moe_set_profile_events.restype = i32
         L.moe_set_profile_events.argtypes = [i32, vp, vp]
         L.moe_workspace_bytes.restype = i32
@@ -102,6 +105,8 @@ def lib():
         L.moe_saturation_threshold_flops.argtypes = [f64, f64, f64]
         L.moe_calibrated_threshold_flops.restype = f64
         L.moe_calibrated_threshold_flops.argtypes = [f64, f64, f64, f64]
+        L.moe_resolve_threshold.restype = i32
+        L.moe_resolve_threshold.argtypes = [f64] * 6 + [ctypes.POINTER(f64), ctypes.POINTER(i32)]
         L.moe_sched_create.restype = i32
         L.moe_sched_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
         L.moe_sched_destroy.restype = None
@@ -185,6 +190,11 @@ def moe_abi_version():
 
 def moe_status_string(status):
     return lib().moe_status_string(status).decode()
+
+
+def moe_init_device():
+    """One-time set-up of the current device (what the first compute call would otherwise do)."""
+    _check(lib().moe_init_device(), "moe_init_device")
 
 
 def moe_set_profile_events(kernel, start_event, stop_event):
@@ -283,6 +293,14 @@ def moe_saturation_threshold_flops(t_ep_seconds, f_gpu_flops, gamma=1.2):
 
 def moe_calibrated_threshold_flops(t_c, t_e, c_dummy_flops, gamma=1.2):
     return lib().moe_calibrated_threshold_flops(t_c, t_e, c_dummy_flops, gamma)
+
+
+def moe_resolve_threshold(pinned, t_c, t_e, f_tok, n_ref, gamma=1.2):
+    """(threshold, unit) with unit 0 = FLOPs, 1 = tokens (App. B.4, delivery and fallback)."""
+    t, u = ctypes.c_double(0.0), ctypes.c_int32(0)
+    _check(lib().moe_resolve_threshold(float(pinned), float(t_c), float(t_e), float(f_tok), float(n_ref), float(gamma),
+                                       ctypes.byref(t), ctypes.byref(u)), "moe_resolve_threshold")
+    return t.value, u.value
 
 
 def moe_prefill_layers_streamed(cfg, layers, x, slots, n_resident=0, ws=None, compute_stream=None,

@@ -1,5 +1,5 @@
 // Weighted combine back to token order: out[t,:] = sum_j w[t,j] * y_perm[inv_perm[t*K+j],:]
-// ("sums their outputs", Sec. 2.3 of the paper).  HBM-bound gather-reduce: every y_perm row is
+// (the sum over a token's k expert outputs, Sec. 2.3 of the paper).  HBM-bound gather-reduce: every y_perm row is
 // read exactly once, 16 bytes per lane, and the K terms are added in slot order in float32, so
 // the result is deterministic.
 #include "common.h"
@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void combine_block16_kernel(const u32x4* __res
 #pragma unroll
             for (int j = 0; j < KU; ++j) {
                 const float s = wt[j0 + j];
-                const float sc = __uint_as_float((k[j] - 14u) << 23);
+                // exponent byte 255 marks a block that held +-Inf: it reads back as NaN
+                const float sc = k[j] == 255u ? __uint_as_float(0x7FC00000u) : __uint_as_float((k[j] - 14u) << 23);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t d = v[j][e >> 1];

@@ -42,6 +42,17 @@ inline int32_t launch_status() {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH_FAILED;
 }
 
+// ---- device.hip : what the library keeps per device.  Filled once per device, under a mutex,
+// by the first call made with that device current (or by moe_init_device): the compute-unit
+// count and the kernels' dynamic-LDS attribute.
+struct DeviceState {
+    int n_cu;
+};
+int32_t device_state(const DeviceState** out);
+// one-time attribute set-up of the kernels that need more than 64 KB of LDS (called by device_state)
+int32_t ffn_mfma_set_attributes();
+int32_t router_mfma_set_attributes();
+
 // Optional per-kernel event bracket (see moe_set_profile_events).
 struct ProfileSlot {
     hipEvent_t start, stop;

@@ -312,7 +312,8 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
                 for (int q = 0; q < 4; ++q) c[q] = __float_as_uint(__builtin_fmaf(r[q], inv, 12582912.f));   // low 16 bits: the code
                 if (!live) continue;
                 if (y_mode == Y_BLOCK16_AS_F32) {
-                    const float sc = __uint_as_float(kf - (14u << 23));         // 2^(k-141)
+                    // 2^(k-141); k = 255 (the block held +-Inf) reads back as NaN, as in the combine
+                    const float sc = kf == (255u << 23) ? __uint_as_float(0x7FC00000u) : __uint_as_float(kf - (14u << 23));
                     f32x4 o;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) o[q] = sc * (float)(int)(short)(c[q] & 0xFFFFu);
@@ -842,6 +843,12 @@ int32_t set_kernel_attributes() {
 
 }  // namespace
 
+int32_t ffn_mfma_set_attributes() {
+    if (set_kernel_attributes<false>() != MOE_OK || set_kernel_attributes<true>() != MOE_OK)
+        return MOE_ERR_LAUNCH_FAILED;
+    return MOE_OK;
+}
+
 size_t ffn_mfma_ws_bytes(const moe_config_t& c) { return ffn_ws_layout(c).total; }
 
 int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* perm,
@@ -877,19 +884,11 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     st = launch_build_tile_order(c, first, offsets, BM, nct_dn, GROUP_ROWS, GROUP_COLS, order_dn, s);
     if (st != MOE_OK) return st;
 
-    // one persistent workgroup per compute unit (the 128 KB of LDS allow no second one)
-    // (compute-unit count and the kernels' LDS attribute are looked up once per device)
-    static int n_cu_of_device[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_ERR_LAUNCH_FAILED;
-    if (n_cu_of_device[dev] == 0) {
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return MOE_ERR_LAUNCH_FAILED;
-        if (set_kernel_attributes<false>() != MOE_OK || set_kernel_attributes<true>() != MOE_OK)
-            return MOE_ERR_LAUNCH_FAILED;
-        n_cu_of_device[dev] = prop.multiProcessorCount;
-    }
-    const int n_cu = n_cu_of_device[dev];
+    // one persistent workgroup per compute unit (the kernels use all 160 KB of its LDS)
+    const DeviceState* dev_state = nullptr;
+    st = device_state(&dev_state);
+    if (st != MOE_OK) return st;
+    const int n_cu = dev_state->n_cu;
     const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
 
     // fp8: quantise the x rows once per token, and carry each sorted row's scale along
@@ -927,8 +926,9 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     g.nct = nct_gu;
     {
         KernelBracket kb(MOE_KERNEL_GATE_UP, s);
-        launch_kernel<MODE_GATE_UP>(fp8, g, grid, s);
+        st = launch_kernel<MODE_GATE_UP>(fp8, g, grid, s);
     }
+    if (st != MOE_OK) return st;
     const char* a_dn = act;
     if (fp8) {   // per-row e4m3 of the bf16 activations
         st = launch_quantize_rows(act, P, c.I, act_q, sa, s);
@@ -964,9 +964,9 @@ int32_t launch_ffn_mfma(const moe_config_t& c, const void* x, const int32_t* per
     d.nct = nct_dn;
     {
         KernelBracket kb(MOE_KERNEL_DOWN, s);
-        launch_kernel<MODE_DOWN>(fp8, d, grid, s);
+        st = launch_kernel<MODE_DOWN>(fp8, d, grid, s);
     }
-    return launch_status();
+    return st;
 }
 
 }  // namespace moe

@@ -1,5 +1,5 @@
 // Router: float32 logits and per-token top-k selection with renormalised softmax weights
-// (the "lightweight router" of Sec. 2.3 of the paper).
+// (the router of Sec. 2.3 of the paper).
 #include "f32_gemm.h"
 
 namespace moe {

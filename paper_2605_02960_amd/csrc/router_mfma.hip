@@ -146,6 +146,13 @@ __global__ __launch_bounds__(R_THREADS) void router_mfma_kernel(const char* __re
 
 }  // namespace
 
+int32_t router_mfma_set_attributes() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&router_mfma_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R_STAGE) == hipSuccess
+               ? MOE_OK
+               : MOE_ERR_LAUNCH_FAILED;
+}
+
 size_t router_mfma_ws_bytes(const moe_config_t& c) {
     return align_up((size_t)3 * c.E * c.H * 2, 256);
 }
@@ -155,15 +162,9 @@ int32_t launch_router_logits_mfma(const moe_config_t& c, const void* x, const fl
     if (c.T == 0) return MOE_OK;
     if ((uint64_t)c.T * c.H * 2 > 0xFFFFFFFFull || (uint64_t)3 * c.E * c.H * 2 > 0xFFFFFFFFull)
         return MOE_ERR_UNSUPPORTED;
-    static bool attr_done[64] = {};   // per device
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_ERR_LAUNCH_FAILED;
-    if (!attr_done[dev]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&router_mfma_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R_STAGE) != hipSuccess)
-            return MOE_ERR_LAUNCH_FAILED;
-        attr_done[dev] = true;
-    }
+    const DeviceState* dev_state = nullptr;
+    const int32_t st = device_state(&dev_state);     // sets this kernel's LDS attribute once per device
+    if (st != MOE_OK) return st;
     uint16_t* w3 = static_cast<uint16_t*>(ws);
     const size_t n = (size_t)c.E * c.H;
     KernelBracket kb(MOE_KERNEL_ROUTER_GEMM, s);

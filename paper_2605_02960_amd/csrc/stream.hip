@@ -1,4 +1,4 @@
-// One-GPU weight streaming of the expert weights (the "one-GPU H2D streaming" mode of the paper's
+// One-GPU weight streaming of the expert weights (the single-GPU host-to-device mode of the paper's
 // weight streaming engine, App. B.1, and the offloading pipeline of Sec. 6.3): the expert weights
 // of all layers live in pinned host memory, the GPU holds a small ring of layer slots, a copy
 // stream prefetches the layers ahead while the compute stream runs moe_prefill_layer on the
@@ -141,6 +141,22 @@ double moe_calibrated_threshold_flops(double t_c, double t_e, double c_dummy_flo
     if (!(t_c > 0.0)) return gamma * c_dummy_flops;              // no calibration: the fallback
     const double ratio = t_e > t_c ? t_e / t_c : 1.0;            // transfers hidden: collapses to gamma * C_dummy
     return gamma * ratio * c_dummy_flops;
+}
+
+int32_t moe_resolve_threshold(double pinned, double t_c, double t_e, double f_tok, double n_ref,
+                              double gamma, double* threshold_out, int32_t* unit_out) {
+    if (!threshold_out || !unit_out) return MOE_ERR_NULL_PTR;
+    if (!(gamma > 0.0) || !(n_ref >= 0.0)) return MOE_ERR_BAD_SHAPE;
+    const bool have_f_tok = f_tok > 0.0;                  // false also for NaN
+    *unit_out = have_f_tok ? MOE_UNIT_FLOPS : MOE_UNIT_TOKENS;
+    if (pinned > 0.0) {                                   // the operator's value wins over any calibration
+        *threshold_out = pinned;
+        return MOE_OK;
+    }
+    // token-unit accounting is the same arithmetic with one unit of work per token
+    const double c_dummy = (have_f_tok ? f_tok : 1.0) * n_ref;
+    *threshold_out = moe_calibrated_threshold_flops(t_c, t_e, c_dummy, gamma);
+    return MOE_OK;
 }
 
 }  // extern "C"

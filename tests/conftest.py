@@ -16,3 +16,11 @@ def pytest_configure(config):
 def tiny_inputs():
     import workloads
     return workloads.generate(workloads.TINY)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    """The C-ABI library, rebuilt when it is missing or older than the sources in the tree (before
+    any test touches a GPU: the build runs hipcc as child processes)."""
+    from paper_2605_02960_amd import build as moe_build
+    return moe_build.ensure_built()

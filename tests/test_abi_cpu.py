@@ -14,8 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 @pytest.fixture(scope="module")
 def L():
-    if not os.path.exists(moe.lib_path()):
-        moe_build.build()
+    moe_build.ensure_built()
     return moe.lib()
 
 

@@ -144,6 +144,21 @@ def test_fp8_qwen3_layer_32k_tokens():
     assert torch.equal(out, r["out"])
 
 
+@pytest.mark.parametrize("T,E,K,zipf", [(96, 8, 2, False), (96, 8, 8, False), (128, 12, 4, True)],
+                         ids=["k2", "k_eq_e", "zipf"])
+def test_fp8_full_contraction_lengths_all_tokens(T, E, K, zipf):
+    """The real contraction lengths of the fp8 configuration (H = 4096, I = 1536) on a batch small
+    enough for the oracle to evaluate every token: every stage gate, and the end-to-end bound of
+    6e-2 * rms asserted over all tokens."""
+    w = workloads.scaled(workloads.QWEN3_32K_FP8, name=f"fp8_full_hi_{T}_{E}_{K}_{int(zipf)}", T=T, E=E, K=K,
+                         zipf_bias=zipf)
+    cfg, g8, r = _fp8_case(w, None, gate_end_to_end=True)
+    out = moe.moe_prefill_layer(cfg, g8["x"], g8["w_router"], g8["bias"], g8["w_gate"], g8["w_up"], g8["w_down"],
+                                g8["s_gate"], g8["s_up"], g8["s_down"])
+    torch.cuda.synchronize()
+    assert torch.equal(out, r["out"])
+
+
 @pytest.mark.parametrize("T,H,E,K,I", [
     (1, 256, 3, 3, 256),       # one token, every expert chosen
     (130, 256, 1, 1, 512),     # one expert, a group that ends two rows into a 64-row block

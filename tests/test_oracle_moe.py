@@ -298,6 +298,56 @@ def test_fp8_path_against_torch_casts():
     assert np.max(np.abs(r["out"] - pure["out"])) > 5e-2 * rms
 
 
+def test_down_project_is_the_second_gemm_of_the_layer():
+    """down_project referees the down-projection stage of the GPU tests, so it is pinned on its
+    own: (1) a case worked by hand; (2) against the y that moe_layer itself returns, for the
+    unrounded, the bf16-activation and the fp8 flavours (fp8: fed with the dequantised activation
+    codes, as the GPU tests feed it); (3) against plain loops and torch's own e4m3 cast of the
+    weights; (4) a wrong expert index, a transposed weight or a skipped dequantisation must fail."""
+    # (1) by hand: Wd_1 = [[1,2],[3,4],[5,6]] (H=3, I=2), a = (10, 1) -> y = (12, 34, 56)
+    wd = np.zeros((2, 3, 2))
+    wd[1] = [[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]]
+    assert mo.down_project(np.array([[10.0, 1.0]]), wd, 1).tolist() == [[12.0, 34.0, 56.0]]
+    assert mo.down_project(np.array([[10.0, 1.0]]), wd, 0).tolist() == [[0.0, 0.0, 0.0]]
+    # (2) the layer's own y, all three flavours
+    w = workloads.scaled(workloads.QWEN3_32K_FP8, T=40, H=128, E=5, K=2, I=64)
+    d = workloads.generate(w)
+    for kw in (dict(), dict(act_rounding="bf16"), dict(fp8=True)):
+        r = _run(d, 2, keep_act=True, **kw)
+        fp8 = bool(kw.get("fp8"))
+        rms = np.sqrt(np.mean(r["y"] ** 2))
+        for e in range(w.E):
+            t, j = np.nonzero(r["topk_idx"] == e)
+            if t.size == 0:
+                continue
+            a = r["act"][t, j]
+            if fp8:     # the layer's down projection reads the per-row e4m3 codes of the bf16 activation
+                q, sc = codecs.quantize_rows_e4m3(a.astype(np.float32))
+                a = codecs.dequantize_rows_e4m3(q, sc)
+            y = mo.down_project(a, d["w_down"], e, fp8=fp8)
+            assert np.max(np.abs(y - r["y"][t, j])) <= 1e-13 * rms, (kw, e)
+            # (4) planted mistakes are visible at the tolerances the GPU stage checks use (1e-4, 1e-3)
+            wrong_e = mo.down_project(a, d["w_down"], (e + 1) % w.E, fp8=fp8)
+            assert np.max(np.abs(wrong_e - r["y"][t, j])) > 0.5 * rms
+            if fp8:
+                no_deq = mo.down_project(a, d["w_down"], e, fp8=False)
+                assert np.max(np.abs(no_deq - r["y"][t, j])) > 1e-2 * rms
+    # (3) plain loops on the stored bf16 weights, and torch's e4m3 cast for the fp8 weights
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal((3, w.I))
+    e = 3
+    wd_e = mo.as_f64(d["w_down"][e])                      # [H, I]
+    loops = np.array([[sum(wd_e[h, i] * a[m, i] for i in range(w.I)) for h in range(w.H)] for m in range(3)])
+    assert np.allclose(mo.down_project(a, d["w_down"], e), loops, rtol=1e-12, atol=1e-14)
+    assert not np.allclose(mo.down_project(a[:, ::-1], d["w_down"], e), loops, rtol=1e-3)
+    w32 = torch.from_numpy(mo.as_f32(d["w_down"][e]))
+    amax = w32.abs().amax(dim=1)
+    s = amax / 448.0
+    wq = (w32 / s[:, None]).clamp(-448, 448).to(torch.float8_e4m3fn).to(torch.float64) * s.to(torch.float64)[:, None]
+    ref8 = torch.from_numpy(a) @ wq.T
+    assert np.allclose(mo.down_project(a, d["w_down"], e, fp8=True), ref8.numpy(), rtol=1e-12, atol=1e-14)
+
+
 def test_workload_recipe():
     w = workloads.scaled(workloads.QWEN3_64K_ZIPF, T=2048, H=256, I=64)
     d = workloads.generate(w)

@@ -11,8 +11,7 @@ from oracle import saturation as sat
 
 @pytest.fixture(scope="module", autouse=True)
 def _lib():
-    if not os.path.exists(moe.lib_path()):
-        moe_build.build()
+    moe_build.ensure_built()
 
 
 def test_flops_per_token_of_the_qwen3_shaped_block():
@@ -52,3 +51,28 @@ def test_eq3_agrees_with_eq1_when_later_layers_are_transfer_bound():
     F = C_dummy / t_c flop/s, Eq. 3 is Eq. 1 at that rate."""
     t_ep, t_c, c = 88e-3, 21e-3, 65536 * sat.flops_per_token(4096, 128, 8, 1536)
     assert sat.threshold_calibrated(t_c, t_ep, c, 1.2) == pytest.approx(sat.threshold_eq1(t_ep, c / t_c, 1.2), rel=1e-14)
+
+
+def test_delivery_and_fallback_rules():
+    """App. B.4: a pinned value wins; before calibration T = gamma * f_tok * n_ref; without f_tok the
+    same rule runs in tokens, and the two units differ exactly by the factor f_tok."""
+    f_tok, n_ref = sat.flops_per_token(4096, 128, 8, 1536), 65536
+    assert sat.resolve_threshold(7.5e15, 10e-3, 25e-3, f_tok, n_ref) == (7.5e15, "flops")       # pinned: no update
+    assert sat.resolve_threshold(None, None, None, f_tok, n_ref, 1.2) == (sat.threshold_fallback(f_tok, n_ref, 1.2), "flops")
+    assert sat.resolve_threshold(0.0, 10e-3, 25e-3, f_tok, n_ref, 1.2) == (sat.threshold_calibrated(10e-3, 25e-3, f_tok * n_ref, 1.2), "flops")
+    t_tok, unit = sat.resolve_threshold(None, 10e-3, 25e-3, None, n_ref, 1.2)
+    assert unit == "tokens" and t_tok == pytest.approx(1.2 * 2.5 * n_ref, rel=1e-15)
+    t_fl, _ = sat.resolve_threshold(None, 10e-3, 25e-3, f_tok, n_ref, 1.2)
+    assert t_fl == pytest.approx(t_tok * f_tok, rel=1e-15)
+    assert sat.resolve_threshold(4096.0, 1.0, 9.0, 0.0, n_ref) == (4096.0, "tokens")
+    # the library's host routine: same values, same unit
+    units = {"flops": 0, "tokens": 1}
+    for args in ((7.5e15, 10e-3, 25e-3, f_tok, n_ref, 1.2), (0.0, 0.0, 0.0, f_tok, n_ref, 1.2),
+                 (0.0, 10e-3, 25e-3, f_tok, n_ref, 1.2), (0.0, 10e-3, 25e-3, 0.0, n_ref, 1.2),
+                 (0.0, 10e-3, 5e-3, float("nan"), n_ref, 1.5), (4096.0, 1.0, 9.0, 0.0, n_ref, 1.2)):
+        want_t, want_u = sat.resolve_threshold(args[0] or None, args[1] or None, args[2], None if not args[3] > 0 else args[3], *args[4:])
+        assert moe.moe_resolve_threshold(*args) == (want_t, units[want_u]), args
+    for bad in ((0.0, 1.0, 1.0, 1.0, 1.0, 0.0), (0.0, 1.0, 1.0, 1.0, -1.0, 1.2)):
+        with pytest.raises(moe.MoEError) as e:
+            moe.moe_resolve_threshold(*bad)
+        assert e.value.status == -2

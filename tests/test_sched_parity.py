@@ -18,8 +18,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 @pytest.fixture(scope="module", autouse=True)
 def _built():
-    if not os.path.exists(moe.lib_path()):
-        moe_build.build()
+    moe_build.ensure_built()
 
 
 def _pack(reqs, B):
@@ -210,3 +209,36 @@ def test_progress_reports_match_oracle():
             moe.moe_sched_tokens_executed(h, loads, 0, -1, f)
     finally:
         moe.moe_sched_destroy(h)
+
+
+def test_token_unit_accounting_is_the_same_round_in_other_units():
+    """App. B.4's last fallback: without f_tok, the threshold and the work counters are kept in
+    tokens (f_tok = 1, no attention term).  With a power-of-two f_tok every product is an exact
+    scaling, so the FLOPs-unit round must make the very same assignments with loads that are
+    exactly f_tok times the token-unit ones; both equal the oracle."""
+    N, B = 4, 16
+    reqs = workloads.generate_requests(200, 12, seed=21)
+    reqs_or = [(p.tolist(), s) for p, s in reqs]
+    t_tok, unit = moe.moe_resolve_threshold(0.0, 10e-3, 25e-3, 0.0, 8192, 1.2)      # no f_tok: tokens
+    assert unit == 1 and t_tok == pytest.approx(1.2 * 2.5 * 8192)
+    f = 2.0 ** 25
+    t_fl, unit = moe.moe_resolve_threshold(0.0, 10e-3, 25e-3, f, 8192, 1.2)
+    assert unit == 0 and t_fl == t_tok * f
+    res = []
+    for f_tok, T in ((1.0, t_tok), (f, t_fl)):
+        h = moe.moe_sched_create(N, B)
+        try:
+            loads = np.zeros(N)
+            res.append((_lib_round(h, reqs, B, T, f_tok, 0, loads), loads))
+        finally:
+            moe.moe_sched_destroy(h)
+    (r_tok, l_tok), (r_fl, l_fl) = res
+    assert r_tok[0].tolist() == r_fl[0].tolist() and r_tok[1].tolist() == r_fl[1].tolist()
+    assert (r_tok[2] * f).tolist() == r_fl[2].tolist() and (l_tok * f).tolist() == l_fl.tolist()
+    r_or = sch.schedule_round(sch.BlockTables(N, B), reqs_or, t_tok, 1, 0)
+    _same(r_tok, l_tok, r_or)
+    # in token units a request's increment is its number of uncached tokens
+    P = np.array([len(p) for p, _ in reqs])
+    S = np.array([s for _, s in reqs])
+    done = r_tok[0] >= 0
+    assert np.array_equal(r_tok[2][done], (P - r_tok[1] + S)[done].astype(np.float64))

@@ -34,8 +34,8 @@ def _pinned(t):
 def test_streamed_layers_against_the_oracle(dtype, n_slots, n_resident):
     fp8 = dtype == "fp8"
     base = workloads.QWEN3_32K_FP8 if fp8 else workloads.QWEN3_8K
-    # fp8: contractions long enough (512 and 1024 terms) for the end-to-end bound to be meaningful
-    shape = dict(T=200, H=512, E=4, K=2, I=1024) if fp8 else dict(T=300, H=256, E=8, K=2, I=256)
+    # fp8: contractions long enough (1024 and 2048 terms) for the end-to-end bound to be meaningful
+    shape = dict(T=128, H=1024, E=4, K=2, I=2048) if fp8 else dict(T=300, H=256, E=8, K=2, I=256)
     w = workloads.scaled(base, name=f"stream_{dtype}", **shape)
     L = 5
     cfg = gu.config_for(w)

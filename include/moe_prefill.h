@@ -56,7 +56,8 @@ typedef enum moe_status {
     MOE_ERR_UNALIGNED = -4,
     MOE_ERR_WORKSPACE_TOO_SMALL = -5,
     MOE_ERR_UNSUPPORTED = -6,
-    MOE_ERR_LAUNCH_FAILED = -7
+    MOE_ERR_LAUNCH_FAILED = -7,
+    MOE_ERR_TOO_LARGE = -8 /* the problem needs more than an entry point's fixed scratch memory */
 } moe_status;
 
 typedef enum moe_dtype {
@@ -191,6 +192,21 @@ int32_t moe_route(const moe_config_t *cfg, const void *x, const float *w_router,
 int32_t moe_permute(const moe_config_t *cfg, const int32_t *topk_idx, const void *x, int32_t *counts,
                     int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm, void *ws,
                     size_t ws_bytes, void *stream);
+
+/* moe_permute for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and therefore have no workspace to pass: the same
+ * kernels and the same results, with the segment counters in a fixed array of
+ * MOE_NOALLOC_SCRATCH_BYTES bytes of device memory inside the library (one copy per GPU, held
+ * until the process ends).  The call allocates and frees nothing.  Configurations whose
+ * moe_workspace_bytes(cfg, MOE_CALL_PERMUTE) = ceil(T*K/2048) * E * 4 exceeds that size return
+ * MOE_ERR_TOO_LARGE and enqueue nothing.  All calls on one GPU share the array: calls that may
+ * overlap on one GPU (different streams, different host threads) race and must be serialised
+ * by the caller.  Nothing in the array has to survive or be cleared between calls.  The first
+ * call on a device looks up the array's address (see moe_init_device). */
+#define MOE_NOALLOC_SCRATCH_BYTES (1u << 20)
+int32_t moe_permute_noalloc(const moe_config_t *cfg, const int32_t *topk_idx, const void *x,
+                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                            void *x_perm, void *stream);
 
 /* Grouped SwiGLU expert FFN over the ragged per-expert row groups (the per-expert
  * GEMMs of Sec. 4.2).  For sorted row p in expert e's group, with

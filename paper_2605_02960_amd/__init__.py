@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     KERNEL_ROUTER_GEMM, KERNEL_TOPK, KERNEL_PERMUTE, KERNEL_GATE_UP, KERNEL_DOWN, KERNEL_COMBINE,
     KERNEL_NAMES, moe_set_profile_events, moe_init_device,
     lib, lib_path, moe_abi_version, moe_status_string, moe_workspace_bytes,
-    moe_quantize_rows_e4m3, moe_route, moe_permute, moe_grouped_ffn, moe_combine,
+    moe_quantize_rows_e4m3, moe_route, moe_permute, moe_permute_noalloc, moe_grouped_ffn, moe_combine,
     moe_prefill_layer, make_config, EXPORTED_SYMBOLS, HipEvents, MoEStreamLayer,
     moe_layer_weight_bytes, moe_prefill_layers_streamed, moe_layer_flops_per_token,
     moe_saturation_threshold_flops, moe_calibrated_threshold_flops, moe_resolve_threshold,

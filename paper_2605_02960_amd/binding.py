@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "moe_layer_weight_bytes", "moe_prefill_layers_streamed", "moe_layer_flops_per_token",
     "moe_saturation_threshold_flops", "moe_calibrated_threshold_flops", "moe_resolve_threshold",
     "moe_abi_version", "moe_status_string", "moe_init_device", "moe_set_profile_events", "moe_workspace_bytes", "moe_quantize_rows_e4m3",
-    "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
+    "moe_route", "moe_permute", "moe_permute_noalloc", "moe_grouped_ffn", "moe_combine", "moe_prefill_layer",
     "moe_sched_create", "moe_sched_destroy", "moe_sched_hash_blocks", "moe_sched_round",
     "moe_sched_blocks_stored", "moe_sched_blocks_evicted", "moe_sched_table_size",
     "moe_sched_tokens_executed",
@@ -86,6 +86,8 @@ def lib():
         L.moe_route.argtypes = [cfgp] + [vp] * 7 + [sz, vp]
         L.moe_permute.restype = i32
         L.moe_permute.argtypes = [cfgp] + [vp] * 8 + [sz, vp]
+        L.moe_permute_noalloc.restype = i32
+        L.moe_permute_noalloc.argtypes = [cfgp] + [vp] * 8
         L.moe_grouped_ffn.restype = i32
         L.moe_grouped_ffn.argtypes = [cfgp] + [vp] * 14 + [sz, vp]
         L.moe_combine.restype = i32
@@ -243,6 +245,15 @@ def moe_permute(cfg, topk_idx, x=None, want_x_perm=False, stream=None):
     _check(lib().moe_permute(ctypes.byref(cfg), _p(topk_idx), _p(x), _p(counts), _p(offsets), _p(perm),
                              _p(inv), _p(xp), _p(ws), n, _stream(stream)), "moe_permute")
     return counts, offsets, perm, inv, xp
+
+
+def moe_permute_noalloc(cfg, topk_idx, out, stream=None):
+    """The allocation-free variant of moe_permute: `out` = (counts, offsets, perm, inv_perm), tensors
+    the caller has allocated beforehand; nothing is allocated here or in the library."""
+    counts, offsets, perm, inv = out
+    _check(lib().moe_permute_noalloc(ctypes.byref(cfg), _p(topk_idx), None, _p(counts), _p(offsets), _p(perm),
+                                     _p(inv), None, _stream(stream)), "moe_permute_noalloc")
+    return out
 
 
 def moe_grouped_ffn(cfg, x, perm, offsets, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down=None,

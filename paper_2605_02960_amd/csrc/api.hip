@@ -99,6 +99,7 @@ const char* moe_status_string(int32_t st) {
         case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MOE_ERR_UNSUPPORTED: return "unsupported configuration";
         case MOE_ERR_LAUNCH_FAILED: return "kernel launch failed";
+        case MOE_ERR_TOO_LARGE: return "problem too large for the entry point's fixed scratch memory";
         default: return "unknown status";
     }
 }

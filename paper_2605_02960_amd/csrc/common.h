@@ -47,6 +47,7 @@ inline int32_t launch_status() {
 // count and the kernels' dynamic-LDS attribute.
 struct DeviceState {
     int n_cu;
+    void* scratch;   // device address of the static scratch array of moe_permute_noalloc on this device
 };
 int32_t device_state(const DeviceState** out);
 // one-time attribute set-up of the kernels that need more than 64 KB of LDS (called by device_state)

@@ -33,8 +33,8 @@ def test_exports_match_header(L):
 
 
 def test_status_strings(L):
-    seen = {moe.moe_status_string(s) for s in range(0, -8, -1)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {moe.moe_status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "ok" in seen
     assert moe.moe_status_string(-99) == "unknown status"
 
 

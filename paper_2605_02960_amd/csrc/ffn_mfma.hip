@@ -516,6 +516,12 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
 
 #define MOE_SGB(MASK_, N_) __builtin_amdgcn_sched_group_barrier(MASK_, N_, 0)
+    // 16 x 16 blocks: the K loop is rotated by a quarter step.  A step's barrier stands before its
+    // last group of 16 MFMAs; behind the barrier the fragments of the NEXT step's first group are
+    // read (they are complete in LDS from the barrier on) while those 16 MFMAs, whose operands
+    // are in registers already, keep the matrix pipe busy.  The next step then starts multiplying
+    // at once instead of waiting for LDS.
+    constexpr bool ROT = !FP8 && BE == 16;
 
     // ---- direct-to-LDS loader: wave w fills rows 32w .. 32w+31 of both operand tiles, 8 rows per
     // instruction; the K offset is added to the lane offsets, the bases are scalar
@@ -649,14 +655,8 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     // One K step: request the weight tile of step KTB_ of CB_ (the next step) and the token
     // tile of step KTA_ of CA_ (the step after), multiply the current slots, wait for everything
     // but the token tile just requested, move on to the next slots
-#define MOE_STEP(CB_, KTB_, CA_, KTA_, FIRST_)                                            \
+#define MOE_ADVANCE_SLOTS()                                                                \
     {                                                                                      \
-        MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                                                    \
-        MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
-        MOE_COMPUTE_STEP(FIRST_);                                                          \
-        MOE_ISSUE_ORDER();                                                                 \
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
-        __syncthreads();                                                                   \
         const uint32_t da = a_rd == 2 ? (uint32_t)(-2 * TILE_BYTES) : (uint32_t)TILE_BYTES; \
         const uint32_t db = b_rd == 1 ? (uint32_t)(-TILE_BYTES) : (uint32_t)TILE_BYTES;    \
         a_rd = a_rd == 2 ? 0 : a_rd + 1;                                                   \
@@ -664,6 +664,57 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         _Pragma("unroll") for (int c = 0; c < NKK; ++c) {                                  \
             ad_a[c] += da;                                                                 \
             ad_b[c] += db;                                                                 \
+        }                                                                                  \
+    }
+    // rotated loop: the fragments of the current slots' first group (token fragments of K slice 0,
+    // weight fragments of its first half)
+#define MOE_ROT_HEAD_READS()                                                               \
+    {                                                                                      \
+        MOE_FREAD_A16(fa0, 0);                                                             \
+        MOE_FREAD_B16(0, 0);                                                               \
+    }
+#define MOE_STEP(CB_, KTB_, CA_, KTA_, FIRST_, LAST_)                                     \
+    {                                                                                      \
+        MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                                                    \
+        MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
+        if constexpr (ROT) {                                                               \
+            if constexpr (FIRST_) MOE_ROT_HEAD_READS();                                    \
+            MOE_FREAD_B16(1, 0);                                                           \
+            MOE_FREAD_A16(fa1, 1);                                                         \
+            MOE_FMFMA16(fa0, 0, FIRST_);                                                   \
+            MOE_FREAD_B16(0, 1);                                                           \
+            MOE_FMFMA16(fa0, 1, FIRST_);                                                   \
+            MOE_FREAD_B16(1, 1);                                                           \
+            MOE_FMFMA16(fa1, 0, false);                                                    \
+            _Pragma("unroll") for (int j = 0; j < NM + NN / 2; ++j) {                      \
+                MOE_SGB(0x008, 2);                                                         \
+                MOE_SGB(0x100, 1);                                                         \
+            }                                                                              \
+            _Pragma("unroll") for (int g = 0; g < 2; ++g) {                                \
+                _Pragma("unroll") for (int j = 0; j < NN / 2; ++j) {                       \
+                    MOE_SGB(0x008, 3);                                                     \
+                    MOE_SGB(0x100, 1);                                                     \
+                }                                                                          \
+                MOE_SGB(0x008, NM * NN / 2 - 3 * NN / 2);                                  \
+            }                                                                              \
+        } else {                                                                           \
+            MOE_COMPUTE_STEP(FIRST_);                                                      \
+            MOE_ISSUE_ORDER();                                                             \
+        }                                                                                  \
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
+        __syncthreads();                                                                   \
+        MOE_ADVANCE_SLOTS();                                                               \
+        if constexpr (ROT) {                                                               \
+            /* a tile's last step leaves the next tile's first fragments to that tile's first  \
+               step: they would have to stay in registers across the epilogue */              \
+            if constexpr (!(LAST_)) MOE_ROT_HEAD_READS();                                  \
+            MOE_FMFMA16(fa1, 1, false);                                                    \
+            if constexpr (!(LAST_)) {                                                      \
+                _Pragma("unroll") for (int j = 0; j < NM + NN / 2; ++j) {                  \
+                    MOE_SGB(0x100, 1);                                                     \
+                    MOE_SGB(0x008, 2);                                                     \
+                }                                                                          \
+            }                                                                              \
         }                                                                                  \
     }
 
@@ -674,14 +725,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
         asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
         __syncthreads();                                                                   \
-        const uint32_t da = a_rd == 2 ? (uint32_t)(-2 * TILE_BYTES) : (uint32_t)TILE_BYTES; \
-        const uint32_t db = b_rd == 1 ? (uint32_t)(-TILE_BYTES) : (uint32_t)TILE_BYTES;    \
-        a_rd = a_rd == 2 ? 0 : a_rd + 1;                                                   \
-        b_rd ^= 1;                                                                         \
-        _Pragma("unroll") for (int c = 0; c < NKK; ++c) {                                  \
-            ad_a[c] += da;                                                                 \
-            ad_b[c] += db;                                                                 \
-        }                                                                                  \
+        MOE_ADVANCE_SLOTS();                                                               \
     }
 
     const int KT = a.KT;   // even, >= 2
@@ -738,24 +782,24 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                 MOE_STEP_IDLE(nxt, 0, nxt, 1);
             }
         } else if (KT > 2) {
-            MOE_STEP(cur, 1, cur, 2, true);
+            MOE_STEP(cur, 1, cur, 2, true, false);
             rec_s = uniform_rec(rec_v);
-            for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP(cur, kt + 1, cur, kt + 2, false);
+            for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP(cur, kt + 1, cur, kt + 2, false, false);
             if (has_next) {
                 fill_a_off<MODE>(nxt, a, tid);
                 fill_b_off<MODE, BE>(nxt, a, tid);
             }
             // last two steps of this tile: their requests reach into the next tile
-            MOE_STEP(cur, KT - 1, nxt, 0, false);
-            MOE_STEP(nxt, 0, nxt, 1, false);
+            MOE_STEP(cur, KT - 1, nxt, 0, false, false);
+            MOE_STEP(nxt, 0, nxt, 1, false, true);
         } else {
             if (has_next) {
                 fill_a_off<MODE>(nxt, a, tid);
                 fill_b_off<MODE, BE>(nxt, a, tid);
             }
-            MOE_STEP(cur, 1, nxt, 0, true);
+            MOE_STEP(cur, 1, nxt, 0, true, false);
             rec_s = uniform_rec(rec_v);
-            MOE_STEP(nxt, 0, nxt, 1, false);
+            MOE_STEP(nxt, 0, nxt, 1, false, true);
         }
 
         if (!idle) store_tile<MODE, FP8>(acc, a, cur, wm_u, wn_u, fr, fq, my_scale);
@@ -770,6 +814,8 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_ISSUE_ORDER
 #undef MOE_STEP
 #undef MOE_STEP_IDLE
+#undef MOE_ADVANCE_SLOTS
+#undef MOE_ROT_HEAD_READS
 #undef MOE_DMA_A
 #undef MOE_DMA_B
 #undef MOE_A_PTR

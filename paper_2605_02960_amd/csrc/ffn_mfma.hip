@@ -189,18 +189,18 @@ struct Blk {
 };
 
 // Weight row held by LDS row R of the weight tile.  A wave's MFMA blocks are interleaved over
-// its output columns (block nj, lane j <-> column NB*j + nj of a column range, NB blocks per
-// range), so that after the MFMA one lane holds NB adjacent output columns of a row and a store
-// instruction writes whole 128-byte lines.
+// its output columns (block nj, lane row j <-> column NB*j + nj, NB blocks), so that after the
+// MFMA one lane holds NB adjacent output columns of a row and a store instruction writes whole
+// 128-byte lines (gate/up: NB = 64 / BE columns of act per lane, the gate and the up block of a
+// column side by side in the lane; down: NB = 128 / BE).
 template <int MODE, int BE>
 __device__ __forceinline__ int weight_col_of_lds_row(int R) {
     if (MODE == MODE_GATE_UP) {          // rows 0..127 gate, 128..255 up; 64 columns per wave
         const int w = R & 63;
         return (R & 64) + (64 / BE) * (w % BE) + w / BE;
     }
-    const int w = R & 127;               // 128 columns per wave, in ranges of 4 blocks
-    const int nj = w / BE;
-    return (R & 128) + (nj >> 2) * (4 * BE) + 4 * (w % BE) + (nj & 3);
+    const int w = R & 127;               // 128 columns per wave: block nj = w / BE, lane row w % BE
+    return (R & 128) + (128 / BE) * (w % BE) + w / BE;
 }
 template <int MODE, int BE>
 __device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int tid) {
@@ -234,97 +234,155 @@ __device__ __forceinline__ int opaque_fq16(int fq) {
     asm volatile("" : "+v"(x));
     return x;
 }
-// Largest magnitude of the 16 values that the 4 lanes of a quad hold (4 each): absolute values as
-// source modifiers, then the maximum with lane ^ 1 and with lane ^ 2 as DPP operands of the max
-// itself (two wait states between writing a register and reading it through DPP).  Every lane of
-// the quad must be active.
-__device__ __forceinline__ float quad_amax4(float a, float b, float c, float d) {
-    float m;
-    asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\t"
-        "v_max_f32 %0, %0, |%4|\n\t"
-        "s_nop 1\n\t"
-        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
-        : "=&v"(m)
-        : "v"(a), "v"(b), "v"(c), "v"(d));
+// Largest magnitude over the lanes that share a 16-column storage block: LP = 2 (a lane and its
+// neighbour lane ^ 1) or LP = 4 (the lanes of a quad), the maximum with the partner lanes taken as
+// DPP operands of the max itself (two wait states between writing a register and reading it
+// through DPP).  Every lane of the group must be active.
+template <int LP>
+__device__ __forceinline__ float block_amax(float m) {
+    static_assert(LP == 2 || LP == 4, "a storage block is held by 2 or 4 lanes");
+    if (LP == 4)
+        asm("s_nop 1\n\t"
+            "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "s_nop 1\n\t"
+            "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+            : "+v"(m));
+    else
+        asm("s_nop 1\n\t"
+            "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf"
+            : "+v"(m));
     return m;
 }
 
-// Down projection epilogue.  A lane holds 4 adjacent columns of a row per column range, the 4
-// lanes of a quad 16 adjacent columns: one storage block.  Block scale: with amax the block's
-// largest magnitude, k = biased exponent of amax (one higher if amax * 2^(141-k) would round to
-// 32768), at least 15; code = rint(v * 2^(141-k)), |code| <= 32767.  The rounding is the float32
-// addition of 1.5 * 2^23 (round to nearest even at integer spacing), fused with the exact scaling.
+// Down projection epilogue.  A lane holds NB = 128 / BE adjacent columns of a row (8 with 16 x 16
+// blocks, 4 with 32 x 32 blocks), so a 16-column storage block lies in LP = 16 / NB neighbouring
+// lanes.  Block scale: with amax the block's largest magnitude, k = biased exponent of amax (one
+// higher if amax * 2^(141-k) would round to 32768), at least 15; code = rint(v * 2^(141-k)),
+// |code| <= 32767.  The rounding is the float32 addition of 1.5 * 2^23 (round to nearest even at
+// integer spacing), fused with the exact scaling.
+// The compact form is written with buffer stores whose range ends at the group's last row: rows
+// of the tile beyond it are dropped by the hardware's range check, so the epilogue has no
+// branches.  The LP lanes of a block take turns over LP consecutive rows in storing the block's
+// exponent byte, so every lane of an exponent store writes one byte.
 template <bool FP8, int y_mode, typename ACC, int NN, int NM>
 __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const MfmaArgs& a,
                                                    const TileCtx& t, int wm, int wn, int fr, int fq,
                                                    float my_scale) {
     constexpr int BE = 64 / NM, VLEN = BE * BE / 64;
-    constexpr int NGRP = NN / 4;                 // column ranges of 4*BE columns, 4 adjacent columns per lane
+    constexpr int NB = NN;                       // adjacent columns per lane
+    constexpr int LP = Y_BLOCK / NB;             // lanes per storage block
+    static_assert(NB * BE == 128 && (NB == 4 || NB == 8), "a wave covers 128 columns");
     const int fq16 = FP8 ? opaque_fq16(fq) : 0;
     const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
     if (nb >= a.N) return;                       // N is a multiple of 128: the whole wave is in or out
-    float sg[NN];
+    float sg[NB];
 #pragma unroll
-    for (int j = 0; j < NN; ++j)
-        sg[j] = FP8 ? a.sB0[(size_t)t.e * a.N + nb + (j >> 2) * (4 * BE) + 4 * fr + (j & 3)] : 1.f;
-    // Addresses: a scalar base per row of the wave (wm, wn, the tile and the loop indices are all
-    // wave-uniform) plus one 32-bit lane offset, so that a store needs no vector address arithmetic.
+    for (int j = 0; j < NB; ++j) sg[j] = FP8 ? a.sB0[(size_t)t.e * a.N + nb + NB * fr + j] : 1.f;
     constexpr uint32_t ESZ = (y_mode == Y_BLOCK16) ? 2 : 4;              // bytes per stored element
     const uint32_t row_bytes = (uint32_t)a.N * ESZ;
-    char* const wave_base = a.C + ((size_t)(t.row0 + wm * 64) * a.N + nb) * ESZ;
-    const uint32_t lane_off = (uint32_t)(fq * 4) * row_bytes + (uint32_t)(4 * fr) * ESZ;
     const uint32_t erow_bytes = (uint32_t)a.N / Y_BLOCK;                 // exponent bytes per row
-    uint8_t* const wave_ebase = (y_mode == Y_BLOCK16) ? a.Cs + (size_t)(t.row0 + wm * 64) * erow_bytes + nb / Y_BLOCK : nullptr;
-    const uint32_t lane_eoff = (uint32_t)(fq * 4) * erow_bytes + (uint32_t)(fr >> 2);
     const int rows_left = t.row_end - t.row0 - wm * 64 - fq * 4;         // rows of the group from this lane's first row on
+    // the row of the wave that acc[..][mi][v] belongs to, less the lane's 4 * fq
+    auto row_of = [](int mi, int v) { return mi * BE + (v >> 2) * 8 + (v & 3); };
+
+    if constexpr (y_mode != Y_BLOCK16) {
+        // float32 y (the staged call and the y tap): plain stores, rows beyond the group skipped
+        char* const wave_base = a.C + ((size_t)(t.row0 + wm * 64) * a.N + nb) * ESZ;
+        const uint32_t lane_off = (uint32_t)(fq * 4) * row_bytes + (uint32_t)(NB * fr) * ESZ;
 #pragma unroll
-    for (int mi = 0; mi < NM; ++mi) {
+        for (int mi = 0; mi < NM; ++mi) {
 #pragma unroll
-        for (int v = 0; v < VLEN; ++v) {
-            const int rc = mi * BE + (v >> 2) * 8 + (v & 3);             // row of the wave, less the lane's 4 * fq
-            const bool live = rc < rows_left;    // the same for all lanes that share a row
-            const float sr = FP8 ? from_lane4(my_scale, (rc << 2) + fq16) : 1.f;
-            char* const row_base = wave_base + (size_t)rc * row_bytes;
+            for (int v = 0; v < VLEN; ++v) {
+                const int rc = row_of(mi, v);
+                const float sr = FP8 ? from_lane4(my_scale, (rc << 2) + fq16) : 1.f;
+                float r[NB];
+                float m = 0.f;
 #pragma unroll
-            for (int grp = 0; grp < NGRP; ++grp) {
-                float r[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    r[q] = acc[grp * 4 + q][mi][v];
-                    if (FP8) r[q] *= sr * sg[grp * 4 + q];
+                for (int j = 0; j < NB; ++j) {
+                    r[j] = acc[j][mi][v];
+                    if (FP8) r[j] *= sr * sg[j];
+                    m = fmaxf(m, fabsf(r[j]));
                 }
-                char* const dst = row_base + grp * (4 * BE) * ESZ + lane_off;
-                if (y_mode == Y_EXACT_F32) {
-                    if (!live) continue;
-                    f32x4 o = {r[0], r[1], r[2], r[3]};
-                    // y is read back (by the combine) only after gigabytes more have gone by: streaming store
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
-                    continue;
-                }
-                const float amax = quad_amax4(r[0], r[1], r[2], r[3]);
-                uint32_t kf = (__float_as_uint(amax) + 0x100u) & 0x7F800000u;   // k << 23
-                kf = max(kf, 15u << 23);
-                const float inv = __uint_as_float((268u << 23) - kf);           // 2^(141-k)
-                uint32_t c[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) c[q] = __float_as_uint(__builtin_fmaf(r[q], inv, 12582912.f));   // low 16 bits: the code
-                if (!live) continue;
                 if (y_mode == Y_BLOCK16_AS_F32) {
+                    const float amax = block_amax<LP>(m);
+                    uint32_t kf = (__float_as_uint(amax) + 0x100u) & 0x7F800000u;   // k << 23
+                    kf = max(kf, 15u << 23);
+                    const float inv = __uint_as_float((268u << 23) - kf);           // 2^(141-k)
                     // 2^(k-141); k = 255 (the block held +-Inf) reads back as NaN, as in the combine
                     const float sc = kf == (255u << 23) ? __uint_as_float(0x7FC00000u) : __uint_as_float(kf - (14u << 23));
-                    f32x4 o;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) o[q] = sc * (float)(int)(short)(c[q] & 0xFFFFu);
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
+                    for (int j = 0; j < NB; ++j) {
+                        const uint32_t c = __float_as_uint(__builtin_fmaf(r[j], inv, 12582912.f));   // low 16 bits: the code
+                        r[j] = sc * (float)(int)(short)(c & 0xFFFFu);
+                    }
+                }
+                if (rc >= rows_left) continue;       // the same for all lanes that share a row
+                f32x4* const dst = reinterpret_cast<f32x4*>(wave_base + (size_t)rc * row_bytes + lane_off);
+#pragma unroll
+                for (int j = 0; j < NB; j += 4)
+                    // y is read back (by the combine) only after gigabytes more have gone by: streaming store
+                    __builtin_nontemporal_store(f32x4{r[j], r[j + 1], r[j + 2], r[j + 3]}, dst + j / 4);
+            }
+        }
+    } else {
+        // Buffer ranges: the tile's rows up to the group's end.  Every store gets a descriptor of
+        // its own that starts at the wave-uniform row of the store (scalar arithmetic), so that
+        // the lane offset is one register for the whole epilogue and the range check still ends
+        // at the group's last row.
+        const uint32_t tile_rows = (uint32_t)(t.row_end - t.row0);
+        char* const codes0 = a.C + (size_t)t.row0 * row_bytes;
+        uint8_t* const exps0 = a.Cs + (size_t)t.row0 * erow_bytes;
+        const int codes_bytes = (int)(tile_rows * row_bytes), exps_bytes = (int)(tile_rows * erow_bytes);
+        const uint32_t lane_row = (uint32_t)(wm * 64 + fq * 4);
+        const int lane_off = (int)(lane_row * row_bytes + (uint32_t)(nb + NB * fr) * ESZ);
+        // exponent bytes: lane j of a block's LP lanes stores row (first row of the run) + j
+        const int lane_eoff = (int)((lane_row + (uint32_t)(fr % LP)) * erow_bytes + (uint32_t)(nb / Y_BLOCK + fr / LP));
+#pragma unroll
+        for (int mi = 0; mi < NM; ++mi) {
+            uint32_t kbits[VLEN];
+#pragma unroll
+            for (int v = 0; v < VLEN; ++v) {
+                const int rc = row_of(mi, v);
+                const float sr = FP8 ? from_lane4(my_scale, (rc << 2) + fq16) : 1.f;
+                float r[NB];
+                float m = 0.f;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    r[j] = acc[j][mi][v];
+                    if (FP8) r[j] *= sr * sg[j];
+                    m = fmaxf(m, fabsf(r[j]));
+                }
+                const float amax = block_amax<LP>(m);
+                uint32_t kf = (__float_as_uint(amax) + 0x100u) & 0x7F800000u;       // k << 23
+                kf = max(kf, 15u << 23);
+                kbits[v] = kf;
+                const float inv = __uint_as_float((268u << 23) - kf);               // 2^(141-k)
+                uint32_t c[NB];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) c[j] = __float_as_uint(__builtin_fmaf(r[j], inv, 12582912.f));   // low 16 bits: the code
+                // low halves of two registers side by side (v_perm_b32: bytes 0-3 from the second source, 4-7 from the first)
+                const int skip = (int)((uint32_t)rc * row_bytes);         // wave-uniform
+                const __amdgpu_buffer_rsrc_t rc_codes = __builtin_amdgcn_make_buffer_rsrc(
+                    codes0 + skip, 0, max(codes_bytes - skip, 0), 0x00020000);
+                const int voff = lane_off;
+                if constexpr (NB == 8) {
+                    const u32x4 o = {__builtin_amdgcn_perm(c[1], c[0], 0x05040100u), __builtin_amdgcn_perm(c[3], c[2], 0x05040100u),
+                                     __builtin_amdgcn_perm(c[5], c[4], 0x05040100u), __builtin_amdgcn_perm(c[7], c[6], 0x05040100u)};
+                    __builtin_amdgcn_raw_buffer_store_b128(o, rc_codes, voff, 0, 2);     // streaming store
                 } else {
                     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-                    // low halves of two registers side by side (v_perm_b32: bytes 0-3 from the second source, 4-7 from the first)
-                    u32x2 o = {__builtin_amdgcn_perm(c[1], c[0], 0x05040100u), __builtin_amdgcn_perm(c[3], c[2], 0x05040100u)};
-                    __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(dst));
-                    if ((fr & 3) == 0)
-                        (wave_ebase + (size_t)rc * erow_bytes + grp * (4 * BE / Y_BLOCK))[lane_eoff] = (uint8_t)(kf >> 23);
+                    const u32x2 o = {__builtin_amdgcn_perm(c[1], c[0], 0x05040100u), __builtin_amdgcn_perm(c[3], c[2], 0x05040100u)};
+                    __builtin_amdgcn_raw_buffer_store_b64(o, rc_codes, voff, 0, 2);
+                }
+                if ((v % LP) == LP - 1) {
+                    // rows v-LP+1 .. v are consecutive rows of the wave (LP divides 4)
+                    uint32_t k = kbits[v - LP + 1];
+#pragma unroll
+                    for (int j = 1; j < LP; ++j) k = (fr % LP) == j ? kbits[v - LP + 1 + j] : k;
+                    const int eskip = (int)((uint32_t)row_of(mi, v - LP + 1) * erow_bytes);   // wave-uniform
+                    const __amdgpu_buffer_rsrc_t rc_exps = __builtin_amdgcn_make_buffer_rsrc(
+                        exps0 + eskip, 0, max(exps_bytes - eskip, 0), 0x00020000);
+                    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(k >> 23), rc_exps, lane_eoff, 0, 0);
                 }
             }
         }
@@ -516,6 +574,31 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
 
 #define MOE_SGB(MASK_, N_) __builtin_amdgcn_sched_group_barrier(MASK_, N_, 0)
+    // fp8 gate/up, rotated loop: a K step is 8 groups of NM MFMAs, group (kk, nj) = K slice kk times
+    // weight block nj.  Token fragments of the two slices sit in xaA and xaB, weight fragments
+    // alternate between wbP and wbQ: the fragment of group i+1 is read while group i multiplies
+    // (-4 % for gate/up; the down kernel, whose epilogue needs more registers, is 3 % slower
+    // with it and keeps the plain order).
+    constexpr bool ROT8 = FP8 && MODE == MODE_GATE_UP;
+    i32x8 xaA[NM], xaB[NM], wbP, wbQ;
+#define MOE_F8_RD_A(DST_, KK_)                                                             \
+    {                                                                                      \
+        _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) DST_[mi] =                       \
+            load_frag8(MOE_A_PTR((KK_) * 2) + mi * BE * ROW_BYTES,                         \
+                       MOE_A_PTR((KK_) * 2 + 1) + mi * BE * ROW_BYTES);                    \
+    }
+#define MOE_F8_RD_B(DST_, KK_, NJ_)                                                        \
+    DST_ = load_frag8(MOE_B_PTR((KK_) * 2) + wb_off(NJ_), MOE_B_PTR((KK_) * 2 + 1) + wb_off(NJ_));
+    /* zero scale operands select the unscaled v_mfma_f32_32x32x64_f8f6f4 */
+#define MOE_F8_MM(XA_, WB_, NJ_, Z_)                                                       \
+    {                                                                                      \
+        _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) {                                \
+            if constexpr (Z_) acc[NJ_][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(  \
+                XA_[mi], WB_, acc_t{}, 0, 0, 0, 0, 0, 0);                                  \
+            else acc[NJ_][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(           \
+                XA_[mi], WB_, acc[NJ_][mi], 0, 0, 0, 0, 0, 0);                             \
+        }                                                                                  \
+    }
     // 16 x 16 blocks: the K loop is rotated by a quarter step.  A step's barrier stands before its
     // last group of 16 MFMAs; behind the barrier the fragments of the NEXT step's first group are
     // read (they are complete in LDS from the barrier on) while those 16 MFMAs, whose operands
@@ -697,6 +780,36 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                 }                                                                          \
                 MOE_SGB(0x008, NM * NN / 2 - 3 * NN / 2);                                  \
             }                                                                              \
+        } else if constexpr (ROT8) {                                                       \
+            static_assert(!FP8 || (NM == 2 && NN == 4), "fp8 step is written for 2 x 4 blocks"); \
+            if constexpr (FIRST_) {                                                        \
+                MOE_F8_RD_A(xaA, 0);                                                       \
+                MOE_F8_RD_B(wbP, 0, 0);                                                    \
+            }                                                                              \
+            MOE_F8_RD_B(wbQ, 0, 1);                                                        \
+            MOE_F8_MM(xaA, wbP, 0, FIRST_);                                                \
+            MOE_F8_RD_B(wbP, 0, 2);                                                        \
+            MOE_F8_RD_A(xaB, 1);                                                           \
+            MOE_F8_MM(xaA, wbQ, 1, FIRST_);                                                \
+            MOE_F8_RD_B(wbQ, 0, 3);                                                        \
+            MOE_F8_MM(xaA, wbP, 2, FIRST_);                                                \
+            MOE_F8_RD_B(wbP, 1, 0);                                                        \
+            MOE_F8_MM(xaA, wbQ, 3, FIRST_);                                                \
+            MOE_F8_RD_B(wbQ, 1, 1);                                                        \
+            MOE_F8_MM(xaB, wbP, 0, false);                                                 \
+            MOE_F8_RD_B(wbP, 1, 2);                                                        \
+            MOE_F8_MM(xaB, wbQ, 1, false);                                                 \
+            MOE_F8_RD_B(wbQ, 1, 3);                                                        \
+            MOE_F8_MM(xaB, wbP, 2, false);                                                 \
+            if constexpr (FIRST_) MOE_SGB(0x100, 2 * NM + 2);                              \
+            MOE_SGB(0x100, 2);                                                             \
+            MOE_SGB(0x008, NM);                                                            \
+            MOE_SGB(0x100, 2 + 2 * NM);                                                    \
+            MOE_SGB(0x008, NM);                                                            \
+            _Pragma("unroll") for (int j = 0; j < 5; ++j) {                                \
+                MOE_SGB(0x100, 2);                                                         \
+                MOE_SGB(0x008, NM);                                                        \
+            }                                                                              \
         } else {                                                                           \
             MOE_COMPUTE_STEP(FIRST_);                                                      \
             MOE_ISSUE_ORDER();                                                             \
@@ -714,6 +827,16 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                     MOE_SGB(0x100, 1);                                                     \
                     MOE_SGB(0x008, 2);                                                     \
                 }                                                                          \
+            }                                                                              \
+        } else if constexpr (ROT8) {                                                       \
+            if constexpr (!(LAST_)) {                                                      \
+                MOE_F8_RD_A(xaA, 0);                                                       \
+                MOE_F8_RD_B(wbP, 0, 0);                                                    \
+            }                                                                              \
+            MOE_F8_MM(xaB, wbQ, 3, false);                                                 \
+            if constexpr (!(LAST_)) {                                                      \
+                MOE_SGB(0x100, 2 * NM + 2);                                                \
+                MOE_SGB(0x008, NM);                                                        \
             }                                                                              \
         }                                                                                  \
     }
@@ -828,6 +951,9 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_FREAD_B16
 #undef MOE_FMFMA16
 #undef MOE_SGB
+#undef MOE_F8_RD_A
+#undef MOE_F8_RD_B
+#undef MOE_F8_MM
 }
 
 struct FfnWs {

@@ -127,26 +127,35 @@ __device__ __forceinline__ void loader_pos(int tid, int i, int& row, int& chunk)
     row = (tid >> 6) * 32 + i * 8 + ((tid & 63) >> 3);
     chunk = (tid & 7) ^ ((row >> 1) & 7);
 }
+// The thread index as a value that the optimiser cannot trace back: the per-tile set-up below
+// derives its lane constants from it anew (a few instructions per tile) instead of holding them
+// in registers, or in spill slots, across the K loop.
+__device__ __forceinline__ int opaque_tid() {
+    int x = threadIdx.x;
+    asm volatile("" : "+v"(x));
+    return x;
+}
 
-// A record that is the same in every lane, moved to scalar registers.  Volatile, so that it stays
-// where it is written (behind a K step's wait for memory) instead of moving up into the MFMA
-// stream, where the wait for its load would stall the matrix pipe.  The trailing s_nop covers the
-// wait states between a vector instruction's scalar result and any kind of reader.
-__device__ __forceinline__ int4 uniform_rec(const int4 r) {
-    int4 o;
-    asm volatile("v_readfirstlane_b32 %0, %4\n\tv_readfirstlane_b32 %1, %5\n\t"
-                 "v_readfirstlane_b32 %2, %6\n\tv_readfirstlane_b32 %3, %7\n\ts_nop 4"
-                 : "=s"(o.x), "=s"(o.y), "=s"(o.z), "=s"(o.w)
-                 : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
-    return o;
+// A tile's 16-byte launch-order record travels on the scalar path, straight into four scalar
+// registers: it occupies no vector registers and no vector-memory wait ever stands for it.  The
+// load and the wait for it are one statement, so that the compiler never sees (and never copies)
+// registers whose load is still in flight; the wave issues it behind a K step's barrier, where
+// the MFMAs it has queued cover the few hundred cycles.  (Scalar loads share the LDS counter;
+// the wait also covers the wave's LDS reads in flight.)
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+__device__ __forceinline__ int4 load_rec(const int4* p) {
+    i32x4 r;
+    asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(r) : "s"(p) : "memory");
+    return make_int4(r[0], r[1], r[2], r[3]);
 }
 // A tile's context from its launch-order record (expert, first row, end row, column tile).  For
 // gate/up this issues the loads of the tile's perm entries; their values (and for down the row
 // numbers) stay in a_off as they are until fill_a_off turns them into byte offsets, so that no
 // wait for them stands between two tiles.
 template <int MODE>
-__device__ __forceinline__ void ctx_from_rec(TileCtx& t, const MfmaArgs& a, const int4 rec, int tid) {
+__device__ __forceinline__ void ctx_from_rec(TileCtx& t, const MfmaArgs& a, const int4 rec, int) {
     constexpr int NCOLS = (MODE == MODE_GATE_UP) ? 128 : 256;
+    const int tid = opaque_tid();
     const int e = rec.x;
     t.e = e;
     t.row0 = rec.y;
@@ -167,7 +176,8 @@ __device__ __forceinline__ void ctx_from_rec(TileCtx& t, const MfmaArgs& a, cons
 // contiguous rows of act, so its offsets are taken from the tile's first row and stay small
 // however many routed rows there are.
 template <int MODE>
-__device__ __forceinline__ void fill_a_off(TileCtx& t, const MfmaArgs& a, int tid) {
+__device__ __forceinline__ void fill_a_off(TileCtx& t, const MfmaArgs& a, int) {
+    const int tid = opaque_tid();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int lrow, lchunk;
@@ -203,7 +213,8 @@ __device__ __forceinline__ int weight_col_of_lds_row(int R) {
     return (R & 128) + (128 / BE) * (w % BE) + w / BE;
 }
 template <int MODE, int BE>
-__device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int tid) {
+__device__ __forceinline__ void fill_b_off(TileCtx& t, const MfmaArgs& a, int) {
+    const int tid = opaque_tid();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int lrow, lchunk;
@@ -231,6 +242,16 @@ __device__ __forceinline__ float from_lane4(float v, int src_lane4) {
 // are used (one add each) instead of being kept in registers across the K loop
 __device__ __forceinline__ int opaque_fq16(int fq) {
     int x = fq << 4;
+    asm volatile("" : "+v"(x));
+    return x;
+}
+// The lane index as a value that the optimiser cannot trace back to the thread index: what an
+// epilogue derives from it (lane offsets of its stores) is computed in the epilogue, a few
+// instructions per tile, instead of being kept in registers, or spilled, across the K loop
+// (a spilled value comes back through a vector memory load, and the wait for it would also wait
+// for every tile request in flight).
+__device__ __forceinline__ int opaque_lane() {
+    int x = threadIdx.x & 63;
     asm volatile("" : "+v"(x));
     return x;
 }
@@ -264,17 +285,25 @@ __device__ __forceinline__ float block_amax(float m) {
 // of the tile beyond it are dropped by the hardware's range check, so the epilogue has no
 // branches.  The LP lanes of a block take turns over LP consecutive rows in storing the block's
 // exponent byte, so every lane of an exponent store writes one byte.
+// Returns the number of vector memory instructions issued when that number is the same for every
+// wave that stores (the compact form), else 0: the tile loop lets that many stores stay in flight
+// across the next tile's first K step.
 template <bool FP8, int y_mode, typename ACC, int NN, int NM>
-__device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const MfmaArgs& a,
+__device__ __forceinline__ int store_tile_down_as(ACC (&acc)[NN][NM], const MfmaArgs& a,
                                                    const TileCtx& t, int wm, int wn, int fr, int fq,
                                                    float my_scale) {
     constexpr int BE = 64 / NM, VLEN = BE * BE / 64;
     constexpr int NB = NN;                       // adjacent columns per lane
     constexpr int LP = Y_BLOCK / NB;             // lanes per storage block
     static_assert(NB * BE == 128 && (NB == 4 || NB == 8), "a wave covers 128 columns");
-    const int fq16 = FP8 ? opaque_fq16(fq) : 0;
+    {
+        const int lane_o = opaque_lane();
+        fr = lane_o % BE;
+        fq = lane_o / BE;
+    }
+    const int fq16 = FP8 ? (fq << 4) : 0;
     const int nb = t.n0 + wn * 128;              // first column of the wave's 128 columns
-    if (nb >= a.N) return;                       // N is a multiple of 128: the whole wave is in or out
+    if (nb >= a.N) return 0;                     // N is a multiple of 128: the whole wave is in or out
     float sg[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) sg[j] = FP8 ? a.sB0[(size_t)t.e * a.N + nb + NB * fr + j] : 1.f;
@@ -386,32 +415,39 @@ __device__ __forceinline__ void store_tile_down_as(ACC (&acc)[NN][NM], const Mfm
                 }
             }
         }
+        return NM * VLEN + NM * VLEN / LP;
     }
+    return 0;
 }
 
 template <bool FP8, typename ACC, int NN, int NM>
-__device__ __forceinline__ void store_tile_down(ACC (&acc)[NN][NM], const MfmaArgs& a,
-                                                const TileCtx& t, int wm, int wn, int fr, int fq,
-                                                float my_scale) {
+__device__ __forceinline__ int store_tile_down(ACC (&acc)[NN][NM], const MfmaArgs& a,
+                                               const TileCtx& t, int wm, int wn, int fr, int fq,
+                                               float my_scale) {
     // one copy of the unrolled epilogue per storage form, chosen once per tile
-    if (a.y_mode == Y_BLOCK16) store_tile_down_as<FP8, Y_BLOCK16>(acc, a, t, wm, wn, fr, fq, my_scale);
-    else if (a.y_mode == Y_BLOCK16_AS_F32) store_tile_down_as<FP8, Y_BLOCK16_AS_F32>(acc, a, t, wm, wn, fr, fq, my_scale);
-    else store_tile_down_as<FP8, Y_EXACT_F32>(acc, a, t, wm, wn, fr, fq, my_scale);
+    if (a.y_mode == Y_BLOCK16) return store_tile_down_as<FP8, Y_BLOCK16>(acc, a, t, wm, wn, fr, fq, my_scale);
+    if (a.y_mode == Y_BLOCK16_AS_F32) return store_tile_down_as<FP8, Y_BLOCK16_AS_F32>(acc, a, t, wm, wn, fr, fq, my_scale);
+    return store_tile_down_as<FP8, Y_EXACT_F32>(acc, a, t, wm, wn, fr, fq, my_scale);
 }
 
 template <int MODE, bool FP8, typename ACC, int NN_, int NM_>
-__device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs& a,
-                                           const TileCtx& t, int wm, int wn, int fr, int fq,
-                                           float my_scale) {
+__device__ __forceinline__ int store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs& a,
+                                          const TileCtx& t, int wm, int wn, int fr, int fq,
+                                          float my_scale) {
     if constexpr (MODE == MODE_DOWN) {
-        store_tile_down<FP8>(acc, a, t, wm, wn, fr, fq, my_scale);
+        return store_tile_down<FP8>(acc, a, t, wm, wn, fr, fq, my_scale);
     } else {
         constexpr int NM = NM_, BE = 64 / NM, VLEN = BE * BE / 64;
         constexpr int NBG = 64 / BE;              // adjacent output columns per lane
         constexpr int NPER = NBG;                                     // adjacent columns per lane
-        const int fq16 = FP8 ? opaque_fq16(fq) : 0;
+        {
+            const int lane_o = opaque_lane();
+            fr = lane_o % BE;
+            fq = lane_o / BE;
+        }
+        const int fq16 = FP8 ? (fq << 4) : 0;
         const int n = t.n0 + wn * 64 + NBG * fr;
-        if (n >= a.N) return;
+        if (n >= a.N) return 0;
         float sg[NPER], su[NPER];   // per-channel scales (fp8): gate or down, and up
 #pragma unroll
         for (int q = 0; q < NPER; ++q) {
@@ -454,6 +490,7 @@ __device__ __forceinline__ void store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs&
                 }
             }
         }
+        return 0;   // rows beyond the group's end are skipped by branches: the count varies
     }
 }
 
@@ -756,9 +793,29 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         MOE_FREAD_A16(fa0, 0);                                                             \
         MOE_FREAD_B16(0, 0);                                                               \
     }
+#define MOE_WAIT_STEP(FIRST_)                                                              \
+    {                                                                                      \
+        if constexpr (FIRST_) {                                                            \
+            /* all but the token tile just requested and the previous epilogue's stores, which \
+               were issued after the weight tile that this wait is for (requests and stores    \
+               complete in issue order) */                                                     \
+            if (n_stores == 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");            \
+            else if (BE == 16) asm volatile("s_waitcnt vmcnt(28)" ::: "memory");           \
+            else asm volatile("s_waitcnt vmcnt(44)" ::: "memory");                         \
+        } else {                                                                           \
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                               \
+        }                                                                                  \
+    }
+    // The record of the tile after the current one is fetched (scalar path) in the current tile's
+    // first K step, right in front of the barrier: the wave has to wait for its LDS reads there
+    // anyway, and most waves wait for the slowest one.
+#define MOE_NEXT_REC(FIRST_)                                                               \
+    {                                                                                      \
+        if constexpr (FIRST_) rec_s = load_rec(a.order + min(L + stride, total - 1));      \
+    }
 #define MOE_STEP(CB_, KTB_, CA_, KTA_, FIRST_, LAST_)                                     \
     {                                                                                      \
-        MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                                                    \
+        if constexpr (!(FIRST_)) MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                           \
         MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
         if constexpr (ROT) {                                                               \
             if constexpr (FIRST_) MOE_ROT_HEAD_READS();                                    \
@@ -814,7 +871,8 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             MOE_COMPUTE_STEP(FIRST_);                                                      \
             MOE_ISSUE_ORDER();                                                             \
         }                                                                                  \
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
+        MOE_WAIT_STEP(FIRST_);                                                             \
+        MOE_NEXT_REC(FIRST_);                                                              \
         __syncthreads();                                                                   \
         MOE_ADVANCE_SLOTS();                                                               \
         if constexpr (ROT) {                                                               \
@@ -842,11 +900,12 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
 
     // the same K step for a wave with nothing to multiply
-#define MOE_STEP_IDLE(CB_, KTB_, CA_, KTA_)                                                \
+#define MOE_STEP_IDLE(CB_, KTB_, CA_, KTA_, FIRST_)                                        \
     {                                                                                      \
-        MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                                                    \
+        if constexpr (!(FIRST_)) MOE_DMA_B(b_rd ^ 1, CB_, KTB_);                           \
         MOE_DMA_A(a_rd == 0 ? 2 : a_rd - 1, CA_, KTA_);                                    \
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                                   \
+        MOE_WAIT_STEP(FIRST_);                                                             \
+        MOE_NEXT_REC(FIRST_);                                                              \
         __syncthreads();                                                                   \
         MOE_ADVANCE_SLOTS();                                                               \
     }
@@ -854,28 +913,28 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     const int KT = a.KT;   // even, >= 2
     const int stride = 8 * nslots;
     TileCtx cur, nxt;
-    ctx_from_rec<MODE>(cur, a, uniform_rec(a.order[L]), tid);
+    ctx_from_rec<MODE>(cur, a, load_rec(a.order + L), tid);
     fill_a_off<MODE>(cur, a, tid);
     fill_b_off<MODE, BE>(cur, a, tid);
-    // The record of the tile after the next one is always on its way, and it is moved to scalar
-    // registers right behind a K step's own wait: nothing at a tile's start waits for memory (a
-    // wait there would also wait for the previous tile's stores).
-    int4 rec_v = a.order[min(L + stride, total - 1)];
     MOE_DMA_A(0, cur, 0);
     MOE_DMA_B(0, cur, 0);
     MOE_DMA_A(1, cur, 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    int4 rec_s = uniform_rec(rec_v);
+    int4 rec_s = load_rec(a.order + min(L + stride, total - 1));
     __syncthreads();
+    MOE_DMA_B(1, cur, 1);
+    int n_stores = 0;   // store instructions this wave issued in the previous tile's epilogue (wave-uniform)
 
     // Invariant at the top of every tile: token slot a_rd holds its K step 0, the next token slot
-    // its step 1, weight slot b_rd its step 0; rec_s is the next tile's record.
+    // its step 1 (or is receiving it), weight slot b_rd its step 0, and the other weight slot is
+    // receiving step 1: that request is made before the previous tile's epilogue, so that the
+    // epilogue's stores are younger than everything the tile's first K step waits for and need
+    // not have completed by then.  rec_s is the next tile's record.
     for (;;) {
         L += stride;
         const bool has_next = L < l_end;
         if (has_next) ctx_from_rec<MODE>(nxt, a, rec_s, tid);
         else nxt = cur;   // nothing follows: the trailing loads re-read this tile (harmless)
-        rec_v = a.order[min(L + stride, total - 1)];
         // fp8: lane j of a wave brings the scale of the wave's row j for the epilogue
         float my_scale = 1.f;
         if (FP8) my_scale = a.sA[min(cur.row0 + wm * 64 + lane, cur.row_end - 1)];
@@ -886,27 +945,24 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         // holds (or is receiving) step k+1, weight slot b_rd holds step k.
         if (idle) {
             if (KT > 2) {
-                MOE_STEP_IDLE(cur, 1, cur, 2);
-                rec_s = uniform_rec(rec_v);
-                for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP_IDLE(cur, kt + 1, cur, kt + 2);
+                MOE_STEP_IDLE(cur, 1, cur, 2, true);
+                for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP_IDLE(cur, kt + 1, cur, kt + 2, false);
                 if (has_next) {
                     fill_a_off<MODE>(nxt, a, tid);
                     fill_b_off<MODE, BE>(nxt, a, tid);
                 }
-                MOE_STEP_IDLE(cur, KT - 1, nxt, 0);
-                MOE_STEP_IDLE(nxt, 0, nxt, 1);
+                MOE_STEP_IDLE(cur, KT - 1, nxt, 0, false);
+                MOE_STEP_IDLE(nxt, 0, nxt, 1, false);
             } else {
                 if (has_next) {
                     fill_a_off<MODE>(nxt, a, tid);
                     fill_b_off<MODE, BE>(nxt, a, tid);
                 }
-                MOE_STEP_IDLE(cur, 1, nxt, 0);
-                rec_s = uniform_rec(rec_v);
-                MOE_STEP_IDLE(nxt, 0, nxt, 1);
+                MOE_STEP_IDLE(cur, 1, nxt, 0, true);
+                MOE_STEP_IDLE(nxt, 0, nxt, 1, false);
             }
         } else if (KT > 2) {
             MOE_STEP(cur, 1, cur, 2, true, false);
-            rec_s = uniform_rec(rec_v);
             for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP(cur, kt + 1, cur, kt + 2, false, false);
             if (has_next) {
                 fill_a_off<MODE>(nxt, a, tid);
@@ -921,11 +977,13 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
                 fill_b_off<MODE, BE>(nxt, a, tid);
             }
             MOE_STEP(cur, 1, nxt, 0, true, false);
-            rec_s = uniform_rec(rec_v);
             MOE_STEP(nxt, 0, nxt, 1, false, true);
         }
 
-        if (!idle) store_tile<MODE, FP8>(acc, a, cur, wm_u, wn_u, fr, fq, my_scale);
+        // the next tile's second weight tile, into the slot that the last K step has just left
+        MOE_DMA_B(b_rd ^ 1, nxt, 1);
+        n_stores = 0;
+        if (!idle) n_stores = __builtin_amdgcn_readfirstlane(store_tile<MODE, FP8>(acc, a, cur, wm_u, wn_u, fr, fq, my_scale));
         if (!has_next) {
             // the last step's token-tile requests are still on their way into this workgroup's LDS
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -937,6 +995,8 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_ISSUE_ORDER
 #undef MOE_STEP
 #undef MOE_STEP_IDLE
+#undef MOE_WAIT_STEP
+#undef MOE_NEXT_REC
 #undef MOE_ADVANCE_SLOTS
 #undef MOE_ROT_HEAD_READS
 #undef MOE_DMA_A

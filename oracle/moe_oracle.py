@@ -131,7 +131,7 @@ def down_project(act_rows, w_down, e, fp8=False):
 # ------------------------------------------------------------------ the layer
 def moe_layer(x, w_router, w_gate, w_up, w_down, k, bias=None, *,
               act_rounding="none", fp8=False, tokens=None, routing_logits=None,
-              keep_act=False):
+              keep_act=False, progress=None):
     """The whole block.  Shapes: x [T,H]; w_router [E,H]; w_gate,w_up [E,I,H];
     w_down [E,H,I]; bias [E] or None.
 
@@ -141,6 +141,8 @@ def moe_layer(x, w_router, w_gate, w_up, w_down, k, bias=None, *,
     routing_logits  optional [T,E] logits to route on instead of the float64
                     ones (used to check integer outputs against selection on a
                     device's own float32 logits).
+    progress        optional callable, called with the expert index after each
+                    expert has been evaluated (long runs report where they are).
     Returns a dict: logits, topk_idx, topk_w, counts, offsets, perm, inv_perm,
     out [len(tokens) or T, H], tokens; with keep_act also act/y per routed row
     of the evaluated tokens, in (token, slot) order."""
@@ -169,6 +171,8 @@ def moe_layer(x, w_router, w_gate, w_up, w_down, k, bias=None, *,
             if act is None:
                 act = np.zeros((tok.size, k, wg.shape[0]), dtype=np.float64)
             act[r, j] = taps["act"]
+        if progress is not None:
+            progress(int(e))
     out = np.einsum("tj,tjh->th", w[tok], y)
     res = dict(logits=logits, topk_idx=idx, topk_w=w, counts=counts, offsets=offsets,
                perm=perm, inv_perm=inv_perm, out=out, tokens=tok)

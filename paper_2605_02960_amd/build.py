@@ -38,9 +38,10 @@ def _run(cmd, verbose):
         print(out)
 
 
-def build(verbose=False, extra=(), out=None, jobs=8):
+def build(verbose=False, extra=(), out=None, jobs=8, link_extra=()):
     """Compiles every source for gfx950 and links the shared library (always, also when one exists).
-    `extra`: more hipcc flags (e.g. -D switches of an experiment), `out`: another output path."""
+    `extra`: more hipcc flags (e.g. -D switches of an experiment, host sanitizers), `out`: another
+    output path, `link_extra`: more flags for the link step."""
     out = out or LIB
     with tempfile.TemporaryDirectory(prefix="moe_build_") as tmp:
         objs = []
@@ -51,7 +52,7 @@ def build(verbose=False, extra=(), out=None, jobs=8):
             cmds.append(["hipcc", *HIPCC_FLAGS, *extra, "-c", src, "-o", obj])
         with ThreadPoolExecutor(max(1, min(jobs, len(cmds)))) as ex:
             list(ex.map(lambda c: _run(c, verbose), cmds))
-        _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out + ".tmp", *objs], verbose)
+        _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, "-o", out + ".tmp", *objs], verbose)
     os.replace(out + ".tmp", out)
     if out == LIB and not extra:
         with open(STAMP, "w") as f:

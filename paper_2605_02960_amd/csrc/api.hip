@@ -145,20 +145,23 @@ int32_t moe_route(const moe_config_t* cfg, const void* x, const float* w_router,
     if (empty) return MOE_OK;
     float* logits = logits_out;
     const bool mfma = route_uses_mfma(*cfg);
+    // with at most 128 experts the matrix-core router selects the top K itself and writes the
+    // logits only on request
+    const bool fused = mfma && router_mfma_fuses_topk(*cfg);
     if (!logits || mfma) {
         if (!ws) return MOE_ERR_NULL_PTR;
         if (!aligned(ws, 256)) return MOE_ERR_UNALIGNED;
         if (ws_bytes < route_ws(*cfg)) return MOE_ERR_WORKSPACE_TOO_SMALL;
-        if (!logits) logits = static_cast<float*>(ws);
+        if (!logits && !fused) logits = static_cast<float*>(ws);
     }
     if (mfma && !aligned(x, 16)) return MOE_ERR_UNALIGNED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (mfma)
-        st = launch_router_logits_mfma(*cfg, x, w_router, bias, logits,
+        st = launch_router_logits_mfma(*cfg, x, w_router, bias, logits, topk_idx, topk_w,
                                        static_cast<char*>(ws) + route_logits_ws(*cfg), s);
     else
         st = launch_router_logits(*cfg, x, w_router, bias, logits, s);
-    if (st != MOE_OK) return st;
+    if (st != MOE_OK || fused) return st;
     return launch_topk(*cfg, logits, topk_idx, topk_w, s);
 }
 
@@ -252,7 +255,10 @@ int32_t moe_prefill_layer(const moe_config_t* cfg, const void* x, const float* w
     char* w8 = static_cast<char*>(ws);
     moe_taps_t t{};
     if (taps) t = *taps;
-    float* logits = t.logits ? t.logits : reinterpret_cast<float*>(w8 + l.logits);
+    // the logits are materialised only for a caller that asks for them, or when the selection is a kernel of its own
+    float* logits = t.logits ? t.logits
+                             : ((route_uses_mfma(*cfg) && router_mfma_fuses_topk(*cfg)) ? nullptr
+                                                                                       : reinterpret_cast<float*>(w8 + l.logits));
     int32_t* idx = t.topk_idx ? t.topk_idx : reinterpret_cast<int32_t*>(w8 + l.idx);
     float* tw = t.topk_w ? t.topk_w : reinterpret_cast<float*>(w8 + l.w);
     int32_t* counts = t.counts ? t.counts : reinterpret_cast<int32_t*>(w8 + l.counts);

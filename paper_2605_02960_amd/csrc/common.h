@@ -76,8 +76,12 @@ int32_t launch_router_logits(const moe_config_t& c, const void* x, const float* 
                              const float* bias, float* logits, hipStream_t s);
 // ---- router_mfma.hip : bf16 activations, float32 router weight split into three bf16 parts
 size_t router_mfma_ws_bytes(const moe_config_t& c);
+// With at most 128 experts the kernel also selects the top K (router_mfma_fuses_topk): logits may
+// then be NULL, and topk_idx / topk_w are written by it instead of by launch_topk.
+bool router_mfma_fuses_topk(const moe_config_t& c);
 int32_t launch_router_logits_mfma(const moe_config_t& c, const void* x, const float* w_router,
-                                  const float* bias, float* logits, void* ws, hipStream_t s);
+                                  const float* bias, float* logits, int32_t* topk_idx, float* topk_w,
+                                  void* ws, hipStream_t s);
 int32_t launch_topk(const moe_config_t& c, const float* logits, int32_t* topk_idx, float* topk_w,
                     hipStream_t s);
 

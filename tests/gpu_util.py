@@ -84,7 +84,7 @@ def check_routing_and_grouping(cfg, d, r, logit_tol=1e-4):
     return dict(logits_gpu=l_gpu, same_set_as_f64=same)
 
 
-def oracle_out(d, cfg, l_gpu, tokens=None, act_rounding="none", fp8=False, keep_act=False):
+def oracle_out(d, cfg, l_gpu, tokens=None, act_rounding="none", fp8=False, keep_act=False, progress=None):
     return mo.moe_layer(d["x"], d["w_router"], d["w_gate"], d["w_up"], d["w_down"], cfg.K, d["bias"],
                         act_rounding=act_rounding, fp8=fp8, tokens=tokens,
-                        routing_logits=l_gpu.astype(np.float64), keep_act=keep_act)
+                        routing_logits=l_gpu.astype(np.float64), keep_act=keep_act, progress=progress)

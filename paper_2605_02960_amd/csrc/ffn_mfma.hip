@@ -454,11 +454,13 @@ __device__ __forceinline__ int store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs& 
             sg[q] = FP8 ? a.sB0[(size_t)t.e * a.N + n + q] : 1.f;
             su[q] = FP8 ? a.sB1[(size_t)t.e * a.N + n + q] : 1.f;
         }
-        // addresses: scalar base per row of the wave + one 32-bit lane offset (see the down epilogue)
+        // Buffer stores whose range ends at the group's last row (see the down epilogue): rows of
+        // the tile beyond it are dropped by the range check, no branches; every store's descriptor
+        // starts at the wave-uniform row of the store, the lane offset is one register.
         const uint32_t row_bytes = (uint32_t)a.N * 2;
-        char* const wave_base = a.C + ((size_t)(t.row0 + wm * 64) * a.N + t.n0 + wn * 64) * 2;
-        const uint32_t lane_off = (uint32_t)(fq * 4) * row_bytes + (uint32_t)(NBG * fr) * 2;
-        const int rows_left = t.row_end - t.row0 - wm * 64 - fq * 4;
+        char* const act0 = a.C + (size_t)t.row0 * row_bytes;
+        const int act_bytes = (int)((uint32_t)(t.row_end - t.row0) * row_bytes);
+        const int lane_off = (int)((uint32_t)(wm * 64 + fq * 4) * row_bytes + (uint32_t)n * 2);
 #pragma unroll
         for (int mi = 0; mi < NM; ++mi) {
 #pragma unroll
@@ -466,31 +468,29 @@ __device__ __forceinline__ int store_tile(ACC (&acc)[NN_][NM_], const MfmaArgs& 
                 const int rc = mi * BE + (v >> 2) * 8 + (v & 3);         // row of the wave, less the lane's 4 * fq
                 // lane j of the wave holds the scale of the wave's row j (all lanes take part)
                 const float sr = FP8 ? from_lane4(my_scale, (rc << 2) + fq16) : 1.f;
-                if (rc >= rows_left) continue;
-                {
-                    float h[NPER];
+                float h[NPER];
 #pragma unroll
-                    for (int q = 0; q < NPER; ++q) {
-                        float g = acc[q][mi][v], u = acc[NBG + q][mi][v];
-                        if (FP8) {
-                            g *= sr * sg[q];
-                            u *= sr * su[q];
-                        }
-                        h[q] = silu_mul(g, u);
+                for (int q = 0; q < NPER; ++q) {
+                    float g = acc[q][mi][v], u = acc[NBG + q][mi][v];
+                    if (FP8) {
+                        g *= sr * sg[q];
+                        u *= sr * su[q];
                     }
-                    char* const dst = wave_base + (size_t)rc * row_bytes + lane_off;
-                    if (NPER == 2) {
-                        *reinterpret_cast<uint32_t*>(dst) = pack2_bf16(h[0], h[1]);
-                    } else {
-                        uint2 o;
-                        o.x = pack2_bf16(h[0], h[1]);
-                        o.y = pack2_bf16(h[NPER - 2], h[NPER - 1]);
-                        *reinterpret_cast<uint2*>(dst) = o;
-                    }
+                    h[q] = silu_mul(g, u);
+                }
+                const int skip = (int)((uint32_t)rc * row_bytes);         // wave-uniform
+                const __amdgpu_buffer_rsrc_t rsrc =
+                    __builtin_amdgcn_make_buffer_rsrc(act0 + skip, 0, max(act_bytes - skip, 0), 0x00020000);
+                if constexpr (NPER == 2) {
+                    __builtin_amdgcn_raw_buffer_store_b32(pack2_bf16(h[0], h[1]), rsrc, lane_off, 0, 0);
+                } else {
+                    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+                    const u32x2 o = {pack2_bf16(h[0], h[1]), pack2_bf16(h[NPER - 2], h[NPER - 1])};
+                    __builtin_amdgcn_raw_buffer_store_b64(o, rsrc, lane_off, 0, 0);
                 }
             }
         }
-        return 0;   // rows beyond the group's end are skipped by branches: the count varies
+        return NM * VLEN;
     }
 }
 
@@ -611,12 +611,11 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     }
 
 #define MOE_SGB(MASK_, N_) __builtin_amdgcn_sched_group_barrier(MASK_, N_, 0)
-    // fp8 gate/up, rotated loop: a K step is 8 groups of NM MFMAs, group (kk, nj) = K slice kk times
+    // fp8, rotated loop: a K step is 8 groups of NM MFMAs, group (kk, nj) = K slice kk times
     // weight block nj.  Token fragments of the two slices sit in xaA and xaB, weight fragments
     // alternate between wbP and wbQ: the fragment of group i+1 is read while group i multiplies
-    // (-4 % for gate/up; the down kernel, whose epilogue needs more registers, is 3 % slower
-    // with it and keeps the plain order).
-    constexpr bool ROT8 = FP8 && MODE == MODE_GATE_UP;
+    // (-4 % for gate/up, -1 % for down).
+    constexpr bool ROT8 = FP8;
     i32x8 xaA[NM], xaB[NM], wbP, wbQ;
 #define MOE_F8_RD_A(DST_, KK_)                                                             \
     {                                                                                      \
@@ -799,9 +798,12 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             /* all but the token tile just requested and the previous epilogue's stores, which \
                were issued after the weight tile that this wait is for (requests and stores    \
                complete in issue order) */                                                     \
-            if (n_stores == 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");            \
-            else if (BE == 16) asm volatile("s_waitcnt vmcnt(28)" ::: "memory");           \
-            else asm volatile("s_waitcnt vmcnt(44)" ::: "memory");                         \
+            /* 4 + n_stores; the epilogues issue 16 or 32 (gate/up) and 24 or 40 (down) stores */ \
+            if (n_stores == 16) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");          \
+            else if (n_stores == 24) asm volatile("s_waitcnt vmcnt(28)" ::: "memory");     \
+            else if (n_stores == 32) asm volatile("s_waitcnt vmcnt(36)" ::: "memory");     \
+            else if (n_stores == 40) asm volatile("s_waitcnt vmcnt(44)" ::: "memory");     \
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                          \
         } else {                                                                           \
             asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                               \
         }                                                                                  \
@@ -933,8 +935,16 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
     for (;;) {
         L += stride;
         const bool has_next = L < l_end;
-        if (has_next) ctx_from_rec<MODE>(nxt, a, rec_s, tid);
-        else nxt = cur;   // nothing follows: the trailing loads re-read this tile (harmless)
+        // The next tile's context (for gate/up: the loads of its perm entries) is set up behind
+        // the first K step, whose fragment prefetch needs the registers; a tile of two K steps
+        // needs it at once.
+        const int4 rec_n = rec_s;
+#define MOE_NEXT_CTX()                                                                     \
+    {                                                                                      \
+        if (has_next) ctx_from_rec<MODE>(nxt, a, rec_n, tid);                              \
+        else nxt = cur; /* nothing follows: the trailing loads re-read this tile (harmless) */ \
+    }
+        if (KT <= 2) MOE_NEXT_CTX();
         // fp8: lane j of a wave brings the scale of the wave's row j for the epilogue
         float my_scale = 1.f;
         if (FP8) my_scale = a.sA[min(cur.row0 + wm * 64 + lane, cur.row_end - 1)];
@@ -946,6 +956,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
         if (idle) {
             if (KT > 2) {
                 MOE_STEP_IDLE(cur, 1, cur, 2, true);
+                MOE_NEXT_CTX();
                 for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP_IDLE(cur, kt + 1, cur, kt + 2, false);
                 if (has_next) {
                     fill_a_off<MODE>(nxt, a, tid);
@@ -963,6 +974,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
             }
         } else if (KT > 2) {
             MOE_STEP(cur, 1, cur, 2, true, false);
+            MOE_NEXT_CTX();
             for (int kt = 1; kt < KT - 2; ++kt) MOE_STEP(cur, kt + 1, cur, kt + 2, false, false);
             if (has_next) {
                 fill_a_off<MODE>(nxt, a, tid);
@@ -997,6 +1009,7 @@ __global__ __launch_bounds__(THREADS) void ffn_mfma_kernel(MfmaArgs a) {
 #undef MOE_STEP_IDLE
 #undef MOE_WAIT_STEP
 #undef MOE_NEXT_REC
+#undef MOE_NEXT_CTX
 #undef MOE_ADVANCE_SLOTS
 #undef MOE_ROT_HEAD_READS
 #undef MOE_DMA_A

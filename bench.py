@@ -43,7 +43,46 @@ def parse():
                     help="host-only: throughput of the frontend's scheduling round (no GPU is used)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="no MoE work: what this GPU sustains with nothing in the way (pure MFMA loops, HBM streaming "
+                         "read and write, the vendor's dense bf16 GEMM); one JSON line")
     return ap.parse_args()
+
+
+def ceilings_mode(torch, moe_build):
+    """Measured device ceilings, to be read beside the datasheet peaks the roofline objects use."""
+    import ctypes
+    torch.cuda.set_device(0)
+    torch.cuda.synchronize()
+    lib = ctypes.CDLL(moe_build.PROBE_LIB)
+    lib.moe_probe_ceilings.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_ulonglong, ctypes.c_int, ctypes.c_int]
+    lib.moe_probe_ceilings.restype = ctypes.c_int
+    r = (ctypes.c_double * 4)()
+    rc = lib.moe_probe_ceilings(r, 8 << 30, 20000, 3)
+    if rc != 0:
+        print(f"bench.py: ceilings probe stopped with hipError_t {rc}", file=sys.stderr)
+        sys.exit(1)
+    n = 8192
+    x = torch.randn((n, n), device="cuda", dtype=torch.bfloat16)
+    y = torch.randn((n, n), device="cuda", dtype=torch.bfloat16) * 0.02
+    for _ in range(5):
+        z = x @ y.T
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(20):
+        z = x @ y.T
+    e.record()
+    torch.cuda.synchronize()
+    del z
+    gemm = 2 * n ** 3 / (s.elapsed_time(e) / 20) / 1e9
+    print(json.dumps({
+        "mode": "ceilings",
+        "mfma_bf16_16x16x32_tflops": round(r[0], 1), "mfma_fp8_32x32x64_tflops": round(r[1], 1),
+        "hbm_stream_read_tbps": round(r[2], 3), "hbm_stream_write_tbps": round(r[3], 3),
+        "vendor_gemm_bf16_8192_tflops": round(gemm, 1),
+        "datasheet": {"bf16_tflops": PEAK_TFLOPS["bf16"], "fp8_tflops": PEAK_TFLOPS["fp8"], "hbm_tbps": 8.0},
+    }))
 
 
 def main():
@@ -64,6 +103,8 @@ def main():
         return sched_mode(a, np, moe, workloads)
 
     moe_build.ensure_built()
+    if a.ceilings:
+        return ceilings_mode(torch, moe_build)
     if a.sweep:
         return sweep(a, np, torch, moe, workloads)
     if a.stream:

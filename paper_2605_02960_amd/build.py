@@ -1,5 +1,6 @@
 """Builds libmoeprefill.so (HIP, gfx950 only) in-tree with hipcc: every source is compiled to an
-object of its own (in parallel), then linked."""
+object of its own (in parallel), then linked.  The device ceilings probe (probe/ceilings.hip, used
+by `bench.py --ceilings` only) becomes a small library of its own, libmoeceilings.so."""
 from concurrent.futures import ThreadPoolExecutor
 import glob
 import hashlib
@@ -12,6 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoeprefill.so")
 STAMP = LIB + ".srchash"
+PROBE_SRC = os.path.join(HERE, "probe", "ceilings.hip")
+PROBE_LIB = os.path.join(HERE, "libmoeceilings.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -54,6 +57,8 @@ def build(verbose=False, extra=(), out=None, jobs=8, link_extra=()):
             list(ex.map(lambda c: _run(c, verbose), cmds))
         _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, "-o", out + ".tmp", *objs], verbose)
     os.replace(out + ".tmp", out)
+    if out == LIB:
+        build_probe(verbose)
     if out == LIB and not extra:
         with open(STAMP, "w") as f:
             f.write(source_hash() + "\n")
@@ -62,9 +67,17 @@ def build(verbose=False, extra=(), out=None, jobs=8, link_extra=()):
     return out
 
 
+def build_probe(verbose=False):
+    """Compiles the ceilings probe into its own shared library."""
+    _run(["hipcc", *HIPCC_FLAGS, "-shared", PROBE_SRC, "-o", PROBE_LIB + ".tmp"], verbose)
+    os.replace(PROBE_LIB + ".tmp", PROBE_LIB)
+    return PROBE_LIB
+
+
 def source_hash():
     """Digest of everything the library is built from (sources, headers, flags)."""
     deps = sources() + sorted(glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h")))
+    deps.append(PROBE_SRC)
     h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
     for p in deps:
         h.update(os.path.basename(p).encode())
@@ -77,7 +90,7 @@ def needs_build():
     """True when the library is missing or was built from other sources than the tree holds now
     (the digest written beside it at build time differs; file times are not trusted: they do not
     survive every copy of the tree)."""
-    if not os.path.exists(LIB) or not os.path.exists(STAMP):
+    if not os.path.exists(LIB) or not os.path.exists(PROBE_LIB) or not os.path.exists(STAMP):
         return True
     with open(STAMP) as f:
         return f.read().strip() != source_hash()

@@ -86,3 +86,10 @@ def test_argument_errors_leave_before_any_launch(L):
                              None, fake, fake, 1 << 30, None) == -1   # fp8 needs scales
     assert L.moe_quantize_rows_e4m3(fake, 4, 12, fake, fake, None) == -2
     assert L.moe_quantize_rows_e4m3(None, 4, 16, fake, fake, None) == -1
+
+
+def test_ceilings_probe_library_loads():
+    """The probe behind `bench.py --ceilings` is a library of its own: it loads and exports its one call
+    (no GPU call is made here)."""
+    lib = ctypes.CDLL(moe_build.PROBE_LIB)
+    assert hasattr(lib, "moe_probe_ceilings")

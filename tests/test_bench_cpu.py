@@ -21,5 +21,7 @@ def test_traffic_figure_names_its_source():
         t = json.load(f)
     for name, rec in t.items():
         assert rec["gate_up_bytes_per_launch"] > 0
-        src = rec["note"].split("see ")[-1].strip()
+        src = rec["source"]
         assert os.path.exists(os.path.join(ROOT, "profiles", src)), src
+        with open(os.path.join(ROOT, "profiles", src)) as f:
+            assert "FETCH_SIZE" in f.read()

@@ -29,7 +29,11 @@ __global__ __launch_bounds__(1024) void build_tile_table_kernel(const int32_t* _
         table[0] = acc;
     }
     __syncthreads();
-    if (first_out && e <= E) first_out[e] = first[e];
+    if (first_out) {
+        // E + 1 entries; with E = 1024 the block has no thread for the last one
+        if (e < E) first_out[e] = first[e];
+        if (e == 0) first_out[E] = first[E];
+    }
     if (e < E) {
         const int32_t t0 = first[e];
         for (int i = 0; i < n; ++i) {

@@ -391,6 +391,28 @@ def test_bf16_degenerate_shapes(T, H, E, K, I):
     assert torch.equal(_fused(cfg, g), r["out"])
 
 
+@pytest.mark.parametrize("T,H,E,K,I,dtype", [
+    (70, 128, 128, 32, 128, "bf16"),     # selection inside the router kernel, both halves of its 2 x 16 result slots
+    (70, 128, 40, 32, 128, "bf16"),      # the same with a ragged expert count
+    (70, 128, 256, 32, 128, "bf16"),     # two expert tiles: router GEMM and selection kernel
+    (70, 128, 1024, 32, 128, "bf16"),    # the largest expert count the configuration allows
+    (50, 64, 64, 32, 64, "fp32"),        # float32 path
+], ids=["e128", "e40", "e256", "e1024", "f32_e64"])
+def test_largest_k(T, H, E, K, I, dtype):
+    """K = 32, the largest the configuration allows: routing bit-exact, weights within 1e-6, layer
+    output within the configuration's bound, fused == staged."""
+    base = workloads.TINY if dtype == "fp32" else workloads.QWEN3_8K
+    w = workloads.scaled(base, name=f"kmax_{dtype}_{E}", T=T, H=H, E=E, K=K, I=I)
+    d, g, cfg, r, info = _layer_case(w)
+    assert int(r["counts"].sum()) == T * K
+    if dtype == "fp32":
+        pure = gu.oracle_out(d, cfg, info["logits_gpu"])
+        assert gu.max_err_over_rms(r["out"].cpu().numpy(), pure["out"]) <= TOL_F32
+    else:
+        _bf16_checks(w, d, g, cfg, r, info, None)
+    assert torch.equal(_fused(cfg, g), r["out"])
+
+
 def _random_bf16_shape(seed):
     rng = np.random.default_rng(1000 + seed)
     H = 128 * int(rng.integers(1, 5))

@@ -162,7 +162,8 @@ def test_fp8_full_contraction_lengths_all_tokens(T, E, K, zipf):
 @pytest.mark.parametrize("T,H,E,K,I", [
     (1, 256, 3, 3, 256),       # one token, every expert chosen
     (130, 256, 1, 1, 512),     # one expert, a group that ends two rows into a 64-row block
-], ids=["one_token_k_eq_e", "one_expert"])
+    (40, 256, 1024, 32, 256),  # the largest expert count and the largest K: mostly empty and one-row groups
+], ids=["one_token_k_eq_e", "one_expert", "e1024_k32"])
 def test_fp8_degenerate_shapes(T, H, E, K, I):
     w = workloads.scaled(workloads.QWEN3_32K_FP8, name=f"fp8_degenerate_{T}_{H}_{E}_{K}_{I}", T=T, H=H, E=E, K=K, I=I)
     cfg, g8, r = _fp8_case(w, None, gate_end_to_end=False)

@@ -93,3 +93,15 @@ def test_ceilings_probe_library_loads():
     (no GPU call is made here)."""
     lib = ctypes.CDLL(moe_build.PROBE_LIB)
     assert hasattr(lib, "moe_probe_ceilings")
+
+
+@pytest.mark.parametrize("compiler,std,lang", [("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "c++")])
+def test_public_headers_are_plain_c(tmp_path, compiler, std, lang):
+    """The boundary is a C ABI: both headers compile as strict C99 and as C++11 with nothing else included."""
+    import subprocess
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "moe_prefill.h"\n#include "moe_sched.h"\n'
+                   "int main(void) { moe_config_t c; (void)c; return 0; }\n")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.check_call([compiler, std, "-x", lang, "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc,
+                           "-fsyntax-only", str(src)])

@@ -62,6 +62,13 @@ def ceilings_mode(torch, moe_build):
     if rc != 0:
         print(f"bench.py: ceilings probe stopped with hipError_t {rc}", file=sys.stderr)
         sys.exit(1)
+    lib.moe_probe_l2_paths.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int]
+    lib.moe_probe_l2_paths.restype = ctypes.c_int
+    l2 = (ctypes.c_double * 2)()
+    rc = lib.moe_probe_l2_paths(l2, 4000, 3)
+    if rc != 0:
+        print(f"bench.py: L2 delivery probe stopped with hipError_t {rc}", file=sys.stderr)
+        sys.exit(1)
     n = 8192
     x = torch.randn((n, n), device="cuda", dtype=torch.bfloat16)
     y = torch.randn((n, n), device="cuda", dtype=torch.bfloat16) * 0.02
@@ -80,6 +87,7 @@ def ceilings_mode(torch, moe_build):
         "mode": "ceilings",
         "mfma_bf16_16x16x32_tflops": round(r[0], 1), "mfma_fp8_32x32x64_tflops": round(r[1], 1),
         "hbm_stream_read_tbps": round(r[2], 3), "hbm_stream_write_tbps": round(r[3], 3),
+        "l2_to_lds_tbps_all_cus": round(l2[0], 2), "l2_to_registers_tbps_all_cus": round(l2[1], 2),
         "vendor_gemm_bf16_8192_tflops": round(gemm, 1),
         "datasheet": {"bf16_tflops": PEAK_TFLOPS["bf16"], "fp8_tflops": PEAK_TFLOPS["fp8"], "hbm_tbps": 8.0},
     }))

@@ -5,6 +5,9 @@
 //   [1] matrix pipe, v_mfma_f32_32x32x64_f8f6f4 with e4m3 operands         TFLOP/s
 //   [2] streaming read of `bytes` of HBM, 16-byte nontemporal loads         TB/s
 //   [3] streaming write of `bytes` of HBM, 16-byte nontemporal stores       TB/s
+// moe_probe_l2_paths: how fast one CU takes in L2-resident lines,
+//   [0] straight into LDS (global_load_lds_dwordx4, the FFN kernels' loader)  TB/s over all CUs
+//   [1] into registers (global_load_dwordx4)                                  TB/s over all CUs
 #include <hip/hip_runtime.h>
 #include <cstdint>
 
@@ -93,6 +96,50 @@ __global__ void fill(uint32_t* p, size_t n) {
     }
 }
 
+// Every workgroup of an XCD (workgroup b runs on XCD b % 8) walks the same 2 MB region, each from
+// its own offset: the lines miss the 32 KB vector cache of the CU and hit the XCD's L2, as the operand
+// panels of the FFN kernels do.  A wave keeps 24 requests of 1 KB in flight.
+constexpr int L2_REGION = 2 << 20;
+
+__global__ __launch_bounds__(WG) void l2_to_lds_loop(const char* src, int iters, float* out) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const char* base = src + (size_t)(blockIdx.x & 7) * L2_REGION;
+    uint32_t off = (uint32_t)(((blockIdx.x >> 3) * 65536 + wave * 8192 + lane * 16) & (L2_REGION - 1));
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + wave * 8192);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst0 + i * 1024), "v"(off + i * 1024), "s"(base)
+                         : "memory", "m0");
+        }
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        off = (off + 65536) & (L2_REGION - 1);          // the next 64 KB stripe of the region
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    out[blockIdx.x * WG + tid] = reinterpret_cast<const float*>(lds)[tid];
+}
+
+__global__ __launch_bounds__(WG) void l2_to_reg_loop(const char* src, int iters, float* out) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const char* base = src + (size_t)(blockIdx.x & 7) * L2_REGION;
+    uint32_t off = (uint32_t)(((blockIdx.x >> 3) * 65536 + wave * 8192 + lane * 16) & (L2_REGION - 1));
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int it = 0; it < iters; ++it) {
+        u32x4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4*>(base + off + i * 1024);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc ^= v[i];
+        off = (off + 65536) & (L2_REGION - 1);
+    }
+    out[blockIdx.x * WG + tid] = __builtin_bit_cast(float, acc[0] ^ acc[1] ^ acc[2] ^ acc[3]);
+}
+
 }  // namespace
 
 #define PROBE_CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { rc = (int)e_; goto done; } } while (0)
@@ -142,6 +189,47 @@ done:
     if (big) (void)hipFree(big);
     if (sink) (void)hipFree(sink);
     if (pool) (void)hipFree(pool);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    return rc;
+}
+
+// L2-resident operand delivery on the current device: result2[0] straight into LDS, result2[1] into
+// registers, TB/s summed over all CUs (one workgroup of 8 waves per CU, 64 KB per workgroup and
+// iteration), best of `reps`.  Returns 0 or the hipError_t that stopped it.
+extern "C" int moe_probe_l2_paths(double* result2, int iters, int reps) {
+    int rc = 0, n_cu = 0, dev = 0;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    char* src = nullptr;
+    float* sink = nullptr;
+    PROBE_CK(hipGetDevice(&dev));
+    PROBE_CK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    PROBE_CK(hipEventCreate(&e0));
+    PROBE_CK(hipEventCreate(&e1));
+    PROBE_CK(hipMalloc(&src, (size_t)8 * L2_REGION + 65536));
+    PROBE_CK(hipMalloc(&sink, (size_t)n_cu * WG * sizeof(float)));
+    PROBE_CK(hipFuncSetAttribute(reinterpret_cast<const void*>(l2_to_lds_loop),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
+    fill<<<1024, 256>>>(reinterpret_cast<uint32_t*>(src), ((size_t)8 * L2_REGION + 65536) / 4);
+    PROBE_CK(hipDeviceSynchronize());
+    for (int which = 0; which < 2; ++which) {
+        float best = 1e30f;
+        for (int r = 0; r < reps + 1; ++r) {             // the first run warms the L2
+            PROBE_CK(hipEventRecord(e0));
+            if (which == 0) l2_to_lds_loop<<<n_cu, WG, 65536>>>(src, iters, sink);
+            else l2_to_reg_loop<<<n_cu, WG>>>(src, iters, sink);
+            PROBE_CK(hipGetLastError());
+            PROBE_CK(hipEventRecord(e1));
+            PROBE_CK(hipEventSynchronize(e1));
+            float ms = 0.f;
+            PROBE_CK(hipEventElapsedTime(&ms, e0, e1));
+            if (r > 0 && ms < best) best = ms;
+        }
+        result2[which] = (double)n_cu * iters * 65536.0 / best / 1e9;
+    }
+done:
+    if (src) (void)hipFree(src);
+    if (sink) (void)hipFree(sink);
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
     return rc;

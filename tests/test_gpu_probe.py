@@ -27,3 +27,20 @@ def test_ceilings_probe_reports_plausible_rates():
     # 256 MiB fits the memory-side cache, so these may exceed what HBM streams; they must still be finite and sane
     assert 0.5 < rd < 40.0
     assert 0.5 < wr < 40.0
+
+
+def test_l2_delivery_probe_reports_plausible_rates():
+    import torch
+    torch.cuda.set_device(0)
+    torch.cuda.synchronize()
+    lib = ctypes.CDLL(moe_build.PROBE_LIB)
+    lib.moe_probe_l2_paths.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int]
+    lib.moe_probe_l2_paths.restype = ctypes.c_int
+    r = (ctypes.c_double * 2)()
+    print("case L2 delivery probe: 500 iterations of 64 KB per CU", flush=True)
+    assert lib.moe_probe_l2_paths(r, 500, 2) == 0
+    to_lds, to_reg = list(r)
+    print(f"  L2 -> LDS {to_lds:.1f} TB/s, L2 -> registers {to_reg:.1f} TB/s (all CUs)")
+    # 256 CUs x 64 B per clock x 2.4 GHz = 39 TB/s is what the L2-to-CU path could carry at most
+    assert 1.0 < to_lds < 45.0
+    assert 1.0 < to_reg < 45.0

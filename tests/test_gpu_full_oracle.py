@@ -1,9 +1,9 @@
 """Full-size parity, every token: the fused call at the three large configurations (235B-A22B
 layer shape: T = 8192 bf16, T = 65536 bf16 with Zipf-like routing, T = 32768 fp8) against the CPU
-oracle evaluated for ALL tokens, not a sample.  The oracle needs minutes of host time per
-configuration (the fp8 one quantises all 384 expert matrices), so these cases run only when
-MOE_FULL_ORACLE=1 is set; the default GPU suite checks the same configurations on sampled tokens.
-Measured values are recorded in the design notes."""
+oracle evaluated for ALL tokens, not a sample.  The two bf16 configurations take about a minute
+together on 16 host cores and always run; the fp8 one (the oracle quantises all 384 expert
+matrices: two minutes, silent under a quiet test runner) runs when MOE_FULL_ORACLE=1 is set, and
+the default suite checks it on sampled tokens.  Measured values are recorded in the design notes."""
 import os
 import time
 
@@ -16,13 +16,14 @@ import workloads
 from oracle import moe_oracle as mo
 import gpu_util as gu
 
-pytestmark = [pytest.mark.gpu,
-              pytest.mark.skipif(os.environ.get("MOE_FULL_ORACLE") != "1", reason="set MOE_FULL_ORACLE=1 (minutes of host time)")]
+pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("w", [workloads.QWEN3_8K, workloads.QWEN3_64K_ZIPF, workloads.QWEN3_32K_FP8], ids=lambda w: w.name)
 def test_every_token_against_the_oracle(w):
     fp8 = w.dtype == "fp8"
+    if fp8 and os.environ.get("MOE_FULL_ORACLE") != "1":
+        pytest.skip("set MOE_FULL_ORACLE=1 (two minutes of host time without output)")
     d = workloads.generate(w)
     g = gu.upload(d)
     cfg = gu.config_for(w)

@@ -32,10 +32,12 @@ def test_permute_noalloc_equals_permute_on_two_calls_in_a_row():
         want = moe.moe_permute(cfg, idx)[:4]
         out = _outputs(cfg)
         torch.cuda.synchronize()
-        before = torch.cuda.memory_allocated()
+        # number of allocation requests torch's allocator has served so far (a count of events: it
+        # cannot fall when the garbage collector frees tensors of earlier tests in between)
+        before = torch.cuda.memory_stats()["allocation.all.allocated"]
         moe.moe_permute_noalloc(cfg, idx, out)
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
         for got, ref in zip(out, want):
             assert torch.equal(got, ref)
         counts, offsets, perm, inv = mo.group_by_expert(idx_h.numpy(), E)
